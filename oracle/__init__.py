@@ -1,0 +1,28 @@
+"""CPU oracle for the AMDP pipeline-stage hot path.
+
+TEST INFRASTRUCTURE ONLY. This package is the plain, slow, obviously-correct
+definition of what the stage computes, written from the paper (AMDP:
+Asynchronous Multi-Directional Pipeline Parallelism): the per-stage schedule
+with version tags (Sections 3.1-3.3, Lemma 1 / Lemma B.1, Appendix B.4), the
+forward and backward pass of a slice of GPT/BERT transformer blocks (Section
+4.1, Table 2), gradient accumulation over a window (Section 3.3) and the Adam
+update (Appendix B.1). It shares no code with the HIP library and is imported
+only by tests, by the smoke check and by the benchmark's cpu_baseline leg;
+the product path never calls it.
+
+Arithmetic is numpy float64 throughout; numpy matmul, scipy's erf and numpy's
+elementwise functions are the only library primitives used as steps.
+
+Pins (see tests, all runnable without a GPU):
+  schedule.generate   Lemma 1 closed form via an independent discrete-event
+                      pipeline simulation; the two worked accumulation examples
+                      of Section 3.3 / Figure 5; brute-force invariants.
+  stage forward       torch.nn.functional fp64 reference ops; causality and
+                      padding-independence properties.
+  stage backward      central finite differences; torch.autograd fp64.
+  accumulate          sum-of-per-minibatch-gradients invariant.
+  adam                closed form of the first step; torch.optim.Adam fp64;
+                      the bias-correction-free form printed in Appendix B.1.
+  bf16 rounding       exhaustive comparison with torch's bfloat16 cast on a
+                      sweep of bit patterns.
+"""

@@ -1,0 +1,222 @@
+"""Pins for oracle/stage.py (no GPU): library reference ops in fp64, central
+finite differences, torch.autograd as a second opinion, structural properties,
+and Table 2's parameter counts."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as TF
+
+import workloads as W
+from oracle import stage as OS
+from oracle.stage import Stage
+
+torch.set_default_dtype(torch.float64)
+
+
+def _setup(key, mb=0):
+    w = W.TINY[key]
+    st = Stage.from_workload(w)
+    theta = W.make_theta(w, st.layout).astype(np.float64)
+    x = W.make_x(w, mb).astype(np.float64)
+    aux = None
+    if w.has_lm_head:
+        aux = W.make_targets(w, mb)
+    elif w.block_kind == W.configs.BERT_POSTLN_BIDIR:
+        aux = np.array([5, 8], dtype=np.int32)[: w.microbatch]
+    dy = None if w.has_lm_head else W.make_dy(w, mb).astype(np.float64) * 1e3
+    return w, st, theta, x, aux, dy
+
+
+# ------------------------------------------------ an independent torch model
+def torch_stage(w, theta_t, x_t, aux):
+    """The same stage written with torch.nn.functional building blocks."""
+    lay = OS.param_layout(w.n_layers, w.d_model, w.d_ffn, w.has_lm_head, w.vocab)
+    p = {}
+    for name, off, r, c in lay:
+        v = theta_t[off:off + r * c]
+        p[name] = v if r == 1 else v.view(r, c)
+    D, H, s, b = w.d_model, w.n_heads, w.seq_len, w.microbatch
+    dh = D // H
+    causal = w.block_kind == W.configs.GPT_PRELN_CAUSAL
+
+    def attn(a, l):
+        qkv = TF.linear(a, p[f"l{l}.w_qkv"].T, p[f"l{l}.b_qkv"])
+        q, k, v = (t.view(b, s, H, dh).transpose(1, 2) for t in qkv.split(D, dim=1))
+        if causal:
+            o = TF.scaled_dot_product_attention(q, k, v, is_causal=True)
+        else:
+            keep = torch.arange(s)[None, :] < torch.as_tensor(np.asarray(aux))[:, None]   # [b, s]
+            o = TF.scaled_dot_product_attention(q, k, v, attn_mask=keep[:, None, None, :])
+        o = o.transpose(1, 2).reshape(b * s, D)
+        return TF.linear(o, p[f"l{l}.w_o"].T, p[f"l{l}.b_o"])
+
+    def mlp(c, l):
+        return TF.linear(TF.gelu(TF.linear(c, p[f"l{l}.w_1"].T, p[f"l{l}.b_1"])),
+                         p[f"l{l}.w_2"].T, p[f"l{l}.b_2"])
+
+    def ln(t, name):
+        return TF.layer_norm(t, (D,), p[name + "_gamma"], p[name + "_beta"], w.ln_eps)
+
+    h = x_t
+    for l in range(w.n_layers):
+        if causal:
+            h = h + attn(ln(h, f"l{l}.ln1"), l)
+            h = h + mlp(ln(h, f"l{l}.ln2"), l)
+        else:
+            h = ln(h + attn(h, l), f"l{l}.ln1")
+            h = ln(h + mlp(h, l), f"l{l}.ln2")
+    if not w.has_lm_head:
+        return h
+    z = ln(h, "lnf")
+    return TF.cross_entropy(z @ p["embed"].T, torch.as_tensor(np.asarray(aux), dtype=torch.long))
+
+
+@pytest.mark.parametrize("key", ["gpt", "bert", "lmhead"])
+def test_forward_matches_library_ops(key):
+    w, st, theta, x, aux, _ = _setup(key)
+    out, _ = st.forward(theta, x, aux)
+    ref = torch_stage(w, torch.tensor(theta), torch.tensor(x), aux).detach().numpy()
+    assert np.allclose(out, ref, rtol=1e-11, atol=1e-12)
+
+
+@pytest.mark.parametrize("key", ["gpt", "bert", "lmhead"])
+def test_backward_matches_autograd(key):
+    w, st, theta, x, aux, dy = _setup(key)
+    _, saved = st.forward(theta, x, aux)
+    dx, g = st.backward(theta, saved, dy)
+    tt = torch.tensor(theta, requires_grad=True)
+    xt = torch.tensor(x, requires_grad=True)
+    out = torch_stage(w, tt, xt, aux)
+    if w.has_lm_head:
+        out.backward()
+    else:
+        out.backward(torch.tensor(dy))
+    assert np.allclose(dx, xt.grad.numpy(), rtol=1e-9, atol=1e-12)
+    assert np.allclose(g, tt.grad.numpy(), rtol=1e-9, atol=1e-12)
+
+
+@pytest.mark.parametrize("key", ["gpt", "bert", "lmhead"])
+def test_backward_finite_differences(key):
+    """Every parameter tensor and dX, central differences in fp64."""
+    w, st, theta, x, aux, dy = _setup(key)
+    _, saved = st.forward(theta, x, aux)
+    dx, g = st.backward(theta, saved, dy)
+
+    def scalar(th, xx):
+        out, _ = st.forward(th, xx, aux)
+        return float(out) if w.has_lm_head else float((out * dy).sum())
+
+    rng = np.random.default_rng(5)
+    h = 1e-5
+    for name, off, r, c in st.layout:
+        for j in rng.choice(r * c, size=min(3, r * c), replace=False):
+            tp, tm = theta.copy(), theta.copy()
+            tp[off + j] += h
+            tm[off + j] -= h
+            fd = (scalar(tp, x) - scalar(tm, x)) / (2 * h)
+            assert abs(fd - g[off + j]) <= 1e-6 * max(1.0, abs(fd)) + 1e-9, (name, j, fd, g[off + j])
+    for j in rng.choice(x.size, size=12, replace=False):
+        xp, xm = x.copy().reshape(-1), x.copy().reshape(-1)
+        xp[j] += h
+        xm[j] -= h
+        fd = (scalar(theta, xp.reshape(x.shape)) - scalar(theta, xm.reshape(x.shape))) / (2 * h)
+        assert abs(fd - dx.reshape(-1)[j]) <= 1e-6 * max(1.0, abs(fd)) + 1e-9
+
+
+def test_mismatched_backward_matches_detached_graph():
+    """Backward with a different parameter version: saved activations are the
+    forward's constants, every weight that appears comes from the new version.
+    Checked on one linear + LayerNorm chain, where that rule has a closed form
+    autograd can evaluate: dX = LNbwd(dY W2^T; saved xhat, gamma2)."""
+    w, st, theta, x, aux, dy = _setup("gpt")
+    theta2 = theta + 0.01 * np.random.default_rng(1).standard_normal(theta.size)
+    _, saved = st.forward(theta, x, aux)
+    dx_a, g_a = st.backward(theta, saved, dy)
+    dx_b, g_b = st.backward(theta2, saved, dy)
+    p2 = OS.unpack(theta2, st.layout)
+    L = w.n_layers - 1
+    # last layer's b_2 / W_2 gradients depend on saved activations only
+    for name, off, r, c in st.layout:
+        if name in (f"l{L}.b_2", f"l{L}.w_2"):
+            assert np.array_equal(g_a[off:off + r * c], g_b[off:off + r * c])
+    # ... and W_1's gradient is c^T (dY W2(v2)^T * gelu'(u_saved)), by hand:
+    ln1, sa, ln2, (c_, u_, h_) = saved[0][L]
+    du = (dy @ p2[f"l{L}.w_2"].T) * OS.gelu_grad(u_)
+    for name, off, r, cc in st.layout:
+        if name == f"l{L}.w_1":
+            assert np.allclose(g_b[off:off + r * cc].reshape(r, cc), c_.T @ du, rtol=1e-12, atol=1e-15)
+    assert not np.allclose(dx_a, dx_b)
+
+
+def test_softmax_rows_and_mask():
+    w, st, theta, x, aux, _ = _setup("bert")
+    _, (saved, _) = st.forward(theta, x, aux)
+    probs = saved[0][1][2]
+    for (seq, h), p in probs.items():
+        assert np.allclose(p.sum(axis=1), 1.0, atol=1e-14)
+        assert np.all(p[:, int(aux[seq]):] == 0.0)
+    w, st, theta, x, aux, _ = _setup("gpt")
+    _, (saved, _) = st.forward(theta, x, aux)
+    for p in saved[0][1][2].values():
+        assert np.all(np.triu(p, 1) == 0.0) and np.allclose(p.sum(axis=1), 1.0, atol=1e-14)
+
+
+def test_causal_independence_of_future():
+    w, st, theta, x, aux, _ = _setup("gpt")
+    y0, _ = st.forward(theta, x)
+    x2 = x.copy()
+    pos = 5
+    for seq in range(w.microbatch):
+        x2[seq * w.seq_len + pos + 1:(seq + 1) * w.seq_len] += 3.0
+    y1, _ = st.forward(theta, x2)
+    for seq in range(w.microbatch):
+        rows = slice(seq * w.seq_len, seq * w.seq_len + pos + 1)
+        assert np.array_equal(y0[rows], y1[rows])
+    assert not np.allclose(y0, y1)
+
+
+def test_padding_independence():
+    w, st, theta, x, aux, _ = _setup("bert")
+    y0, _ = st.forward(theta, x, aux)
+    x2 = x.copy()
+    for seq in range(w.microbatch):
+        x2[seq * w.seq_len + int(aux[seq]):(seq + 1) * w.seq_len] -= 2.0
+    y1, _ = st.forward(theta, x2, aux)
+    for seq in range(w.microbatch):
+        rows = slice(seq * w.seq_len, seq * w.seq_len + int(aux[seq]))
+        assert np.allclose(y0[rows], y1[rows], rtol=0, atol=1e-13)
+
+
+def test_uniform_logits_loss_is_log_vocab():
+    w, st, theta, x, aux, _ = _setup("lmhead")
+    th = theta.copy()
+    for name, off, r, c in st.layout:
+        if name == "embed":
+            th[off:off + r * c] = 0.0
+    loss, saved = st.forward(th, x, aux)
+    assert abs(loss - np.log(w.vocab)) < 1e-12
+    _, g = st.backward(th, saved)
+    for name, off, r, c in st.layout:
+        if name == "embed":     # rows sum over vocab to zero: sum_v (p_v - onehot_v) = 0
+            assert np.allclose(g[off:off + r * c].reshape(r, c).sum(axis=0), 0.0, atol=1e-14)
+
+
+def test_table2_parameter_counts(golden_dir):
+    facts = json.load(open(os.path.join(golden_dir, "paper_schedule_facts.json")))["table2_parameter_counts"]
+    g = facts["gpt"]
+    h = g["hidden"]
+    per_layer = OS.n_params(OS.param_layout(1, h, 4 * h))
+    assert per_layer == 12 * h * h + 13 * h
+    # GPT: layers + padded vocabulary embedding + learned positions + final LayerNorm
+    assert g["layers"] * per_layer + 50304 * h + g["seq"] * h + 2 * h == g["params"]
+    # the stage layout with an LM head reproduces layers + embedding + final LN
+    assert OS.n_params(OS.param_layout(g["layers"], h, 4 * h, True, 50304)) + g["seq"] * h == g["params"]
+    # BERT: layers + embeddings (vocab 29056, 512 positions, 2 token types) + embedding LN
+    #       + pooler + LM-head transform (dense + LN + vocab bias) + 2-way sentence head
+    b = facts["bert"]
+    bert = (b["layers"] * per_layer + 29056 * h + 512 * h + 2 * h + (h * h + h)
+            + (h * h + h) + 2 * h + 29056 + (2 * h + 2) + 2 * h)
+    assert bert == b["params"]

@@ -1,0 +1,71 @@
+"""Seeded random inputs, shaped and distributed like the stage's real traffic.
+
+A middle pipeline stage never sees tokens, only activations from its
+predecessor and gradients from its successor, so the stand-in for the paper's
+text corpora (Section 4.1) is by distribution: activations ~ N(0,1), upstream
+gradients ~ N(0, (1e-3)^2), weights ~ N(0, 0.02^2) with LayerNorm gains centred
+on one. Everything is drawn from numpy's PCG64 with
+seed = 296640 + config number + 1000 * buffer index.
+"""
+import numpy as np
+
+from .configs import BF16
+
+SEED_BASE = 29664 * 10
+
+
+def seed_for(workload, k=0):
+    return SEED_BASE + workload.number + 1000 * k
+
+
+def quantize_bf16_grid(a):
+    """Snap fp32 values to the nearest value representable in bfloat16
+    (ties to even), returned as fp32. Used so that both consumers of a 16-bit
+    workload start from bit-identical inputs."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    u = a.view(np.uint32).astype(np.uint64)
+    lsb = (u >> 16) & 1
+    u = (u + 0x7FFF + lsb) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+def _maybe_q(workload, a):
+    return quantize_bf16_grid(a) if workload.dtype == BF16 else a.astype(np.float32)
+
+
+def make_theta(workload, layout):
+    """Flat fp32 master parameters. `layout` is a list of
+    (name, offset, rows, cols) records supplied by the caller; entries whose
+    name starts with 'ln' and ends with 'gamma' are drawn around one."""
+    total = max(off + r * c for _, off, r, c in layout)
+    rng = np.random.default_rng(seed_for(workload, 0))
+    theta = (0.02 * rng.standard_normal(total)).astype(np.float32)
+    for name, off, r, c in layout:
+        if name.endswith("gamma"):
+            theta[off:off + r * c] += 1.0
+    return theta
+
+
+def make_x(workload, mb):
+    rng = np.random.default_rng(seed_for(workload, 1 + 2 * mb))
+    x = rng.standard_normal((workload.tokens, workload.d_model)).astype(np.float32)
+    return _maybe_q(workload, x)
+
+
+def make_dy(workload, mb):
+    rng = np.random.default_rng(seed_for(workload, 2 + 2 * mb))
+    dy = (1e-3 * rng.standard_normal((workload.tokens, workload.d_model))).astype(np.float32)
+    return _maybe_q(workload, dy)
+
+
+def make_valid_len(workload, mb):
+    """Per-sequence number of valid (unpadded) key positions, uniform on
+    [seq/4, seq] inclusive (128..512 at sequence length 512)."""
+    rng = np.random.default_rng(seed_for(workload, 500000 + mb))
+    lo = max(1, workload.seq_len // 4)
+    return rng.integers(lo, workload.seq_len + 1, size=workload.microbatch).astype(np.int32)
+
+
+def make_targets(workload, mb):
+    rng = np.random.default_rng(seed_for(workload, 700000 + mb))
+    return rng.integers(0, workload.vocab, size=workload.tokens).astype(np.int32)
