@@ -29,7 +29,8 @@ class StageRun:
                        grad_scale=grad_scale, bias_correction=bias_correction)
         self._publish = optim.round_to_bf16 if storage == "bf16" else optim.round_to_fp32
         self.versions = {0: self._publish(self.theta)}
-        self._retired = set()  # versions whose last reader has run
+        self._pins = {}      # version -> in-flight minibatches whose forward read it
+        self._fwd_version = {}
         self.saved = {}      # mb -> saved activations
         self.grads = {}      # mb -> per-minibatch flat gradient, until accumulated
 
@@ -38,11 +39,15 @@ class StageRun:
             raise RuntimeError("minibatch already in flight")
         out, saved = self.stage.forward(self.versions[version], x, aux)
         self.saved[mb] = saved
+        self._fwd_version[mb] = version
+        self._pins[version] = self._pins.get(version, 0) + 1
         return out
 
     def backward(self, mb, version, dy=None):
         dx, g = self.stage.backward(self.versions[version], self.saved[mb], dy)
         self.grads[mb] = g
+        self._pins[self._fwd_version.pop(mb)] -= 1
+        self._drop_unpinned()
         return dx, g
 
     def accumulate(self, mb):
@@ -56,19 +61,17 @@ class StageRun:
         self.G = np.zeros_like(self.G)
         self.version += 1
         self.versions[self.version] = self._publish(self.theta)
-        self._drop_retired()
+        self._drop_unpinned()
         return self.version
 
-    def release(self, version):
-        """The last reader of `version` has run. The current version stays
-        resident until an update replaces it."""
-        self._retired.add(version)
-        self._drop_retired()
-
-    def _drop_retired(self):
-        for v in [v for v in self._retired if v != self.version]:
-            self.versions.pop(v, None)
-            self._retired.discard(v)
+    def _drop_unpinned(self):
+        """The stash rule (Section 1 describes parameter stashing as keeping
+        the forward's parameters for the matching backward): a version stays
+        resident while it is current or while a minibatch whose forward read
+        it still awaits its backward."""
+        for v in list(self.versions):
+            if v != self.version and self._pins.get(v, 0) == 0:
+                del self.versions[v]
 
     def run(self, events, x_of, dy_of, aux_of=lambda mb: None, observer=None):
         """Execute an event list. x_of/dy_of/aux_of map a minibatch id to its
@@ -88,7 +91,5 @@ class StageRun:
                 self.update()
                 payload = {"G_applied": g_before, "theta": self.theta, "m": self.m, "v": self.v,
                            "version": self.version}
-            if ev.kind in (S.F, S.B) and (ev.flags & S.FLAG_LAST_USE):
-                self.release(ev.version)
             if observer is not None:
                 observer(ev, payload)
