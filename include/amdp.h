@@ -1,0 +1,246 @@
+/*
+ * amdp.h -- C ABI of the AMDP pipeline-stage library for AMD MI355X (gfx950).
+ *
+ * The library implements the work ONE pipeline stage performs on its own GPU
+ * under AMDP (Asynchronous Multi-Directional Pipeline parallelism): forward and
+ * backward of a contiguous slice of GPT- or BERT-style transformer blocks, each
+ * with the weight version the schedule assigns it; accumulation of gradients
+ * over a window of minibatches; one fused Adam update per window; and the
+ * host-side generator of the stage's event order (paper Sections 3.1-3.3,
+ * Lemma 1, Appendix B.1, B.4).
+ *
+ * Conventions
+ *   - Every function returns int: AMDP_OK (0) or a negative AMDP_E_* code. No
+ *     exceptions, no aborts, nothing printed. amdp_strerror() names a code.
+ *   - "host" pointers are ordinary process memory. "device" pointers are HIP
+ *     device memory on the GPU that was current when the stage was created.
+ *     All device pointers are owned by the caller and only borrowed for the
+ *     duration of the enqueued work.
+ *   - The library never allocates device memory. The caller asks
+ *     amdp_stage_workspace_bytes(), allocates that many bytes (256-byte
+ *     aligned) and hands them to amdp_stage_create(); the workspace must stay
+ *     alive and untouched until amdp_stage_destroy().
+ *   - All GPU work is enqueued on the HIP stream given at create time and is
+ *     ordered by that stream. The library never synchronises; outputs are
+ *     valid once the stream reaches them.
+ *   - State checks happen before anything is enqueued: a call that returns an
+ *     error has changed nothing.
+ *   - Structs start with `struct_size` = sizeof(the struct) as compiled by the
+ *     caller; a mismatch is AMDP_E_INVAL.
+ */
+#ifndef AMDP_H
+#define AMDP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AMDP_OK            0
+#define AMDP_E_INVAL      -1  /* bad argument or configuration, null pointer, workspace too small */
+#define AMDP_E_MB_STATE   -2  /* minibatch in the wrong state: backward/accumulate without forward,
+                                 second forward of a live minibatch, staging buffer still occupied */
+#define AMDP_E_NO_SLOT    -3  /* more minibatches in flight than act_slots: the in-flight bound of
+                                 the schedule was broken */
+#define AMDP_E_VERSION    -4  /* requested weight version is neither current nor stashed */
+#define AMDP_E_STASH_FULL -5  /* an update needs a free version slot and every slot is still read
+                                 by an in-flight minibatch */
+#define AMDP_E_HIP        -6  /* a HIP call or kernel launch failed */
+#define AMDP_E_CAPACITY   -7  /* caller's output array is too small; *n_out holds the need */
+
+const char* amdp_strerror(int code);
+
+/* ------------------------------------------------------------------------
+ * Schedule generator (host only, integers only, no GPU needed)
+ *
+ * Emits the ordered events of one logical stage i of a depth-d pipeline whose
+ * P concurrent pipelines (Section 3.2) are merged onto it round by round:
+ *   - stage i warms up with w = min(n, d-i) forwards per pipeline, n being the
+ *     number of minibatches stage 0 may inject before its first backward
+ *     (Section 3.1; AMDP fixes n = 2), then alternates backward / forward;
+ *   - minibatch m belongs to pipeline m mod P and accumulation window m div T;
+ *   - each backward is followed at once by the accumulation of its gradient;
+ *   - one update closes each window of T minibatches (Section 3.3). With
+ *     AMDP_U_NEXT_BUBBLE it is applied immediately before the first backward of
+ *     the next window ("during the next bubble"); with AMDP_U_EAGER right after
+ *     the window's last accumulation (the setting of Lemma 1).
+ * Version tags: a forward reads version = number of updates applied before
+ * it. A backward reads its forward's version (AMDP_BWD_STASHED) or the
+ * version current when it runs (AMDP_BWD_CURRENT; current - forward's tag is
+ * the parameter mismatch of Section 3.1). An update event carries the version
+ * it produces. Event count is 3*M + ceil(M/T).
+ * ------------------------------------------------------------------------ */
+
+enum { AMDP_EV_F = 0, AMDP_EV_B = 1, AMDP_EV_A = 2, AMDP_EV_U = 3 };
+enum { AMDP_U_NEXT_BUBBLE = 0, AMDP_U_EAGER = 1 };
+enum { AMDP_BWD_STASHED = 0, AMDP_BWD_CURRENT = 1 };
+
+#define AMDP_FLAG_LAST_USE       1u  /* F/B: no later event reads this version */
+#define AMDP_FLAG_PARTIAL_WINDOW 2u  /* U: the window it closes holds fewer than T minibatches */
+
+typedef struct amdp_event_t {
+    uint8_t  kind;      /* AMDP_EV_* */
+    uint8_t  pipeline;  /* m mod P for F/B/A, 0 for U */
+    uint16_t flags;     /* AMDP_FLAG_* */
+    int32_t  mb;        /* F/B/A: global minibatch id; U: window index */
+    uint32_t version;   /* F/B: version read; A: 0; U: version produced */
+} amdp_event_t;
+
+typedef struct amdp_sched_params_t {
+    uint32_t struct_size;
+    int32_t depth;            /* d >= 1 */
+    int32_t pipelines;        /* P >= 1 (at most 256) */
+    int32_t stage;            /* i in [0, d) */
+    int32_t inject_limit;     /* n >= 1; AMDP uses 2 */
+    int32_t threshold;        /* T >= 1, minibatches per update */
+    int32_t n_minibatches;    /* M >= 0 */
+    int32_t update_placement; /* AMDP_U_* */
+    int32_t bwd_version;      /* AMDP_BWD_* */
+} amdp_sched_params_t;
+
+/* Writes up to `cap` events to `out` (host). *n_out (host) receives the number
+ * of events the schedule has; if it exceeds cap nothing is written and
+ * AMDP_E_CAPACITY is returned (call with out = NULL, cap = 0 to size). */
+int amdp_schedule_generate(const amdp_sched_params_t* params, amdp_event_t* out, size_t cap,
+                           size_t* n_out);
+
+typedef struct amdp_sched_stats_t {
+    uint32_t struct_size;
+    int32_t max_inflight;               /* forwards not yet backwarded, all pipelines */
+    int32_t max_inflight_per_pipeline;
+    int32_t max_mismatch;               /* updates between F(m) and B(m), Section 3.1 */
+    int32_t max_affected_per_window;    /* minibatches of one window with mismatch > 0 */
+    int32_t max_live_versions;          /* current + older versions still to be read */
+} amdp_sched_stats_t;
+
+/* Bounds of an event list (host arrays). `threshold` groups minibatches into
+ * windows for max_affected_per_window. AMDP_E_INVAL on a malformed list
+ * (backward before forward, unknown kind). */
+int amdp_schedule_stats(const amdp_event_t* events, size_t n, int32_t threshold,
+                        amdp_sched_stats_t* out);
+
+/* Chimera-style placement of Section 3.2: stage i of pipeline j runs on GPU
+ * (2j+i) mod d for even j and (2j-i+d+1) mod d for odd j. Host only. */
+int amdp_stage_map(int32_t depth, int32_t pipeline, int32_t stage, int32_t* gpu_out);
+
+/* ------------------------------------------------------------------------
+ * Stage
+ * ------------------------------------------------------------------------ */
+
+enum { AMDP_BLOCK_GPT_PRELN_CAUSAL = 0, AMDP_BLOCK_BERT_POSTLN_BIDIR = 1 };
+enum { AMDP_FP32 = 0, AMDP_BF16 = 1 };
+
+typedef struct amdp_stage_config_t {
+    uint32_t struct_size;
+    int32_t block_kind;   /* AMDP_BLOCK_* */
+    int32_t n_layers;     /* L >= 1 */
+    int32_t d_model;      /* D, multiple of n_heads */
+    int32_t n_heads;      /* H */
+    int32_t d_ffn;        /* F */
+    int32_t seq_len;      /* s */
+    int32_t microbatch;   /* b sequences per minibatch; tokens N = b*s */
+    int32_t dtype;        /* AMDP_FP32: activations and weight versions in fp32;
+                             AMDP_BF16: both in bfloat16, fp32 accumulation, statistics, master */
+    int32_t has_lm_head;  /* final LayerNorm + tied vocabulary projection + cross-entropy */
+    int32_t vocab;        /* V when has_lm_head */
+    float   ln_eps;
+    int32_t act_slots;    /* minibatches that may be in flight (>= w*P) */
+    int32_t stash_slots;  /* weight versions kept besides the current one (>= 1) */
+} amdp_stage_config_t;
+
+typedef struct amdp_stage amdp_stage_t;
+
+/* Parameters live in one flat vector. Per layer, in order: ln1 gamma, beta [D];
+ * W_qkv [D,3D] (columns Q|K|V, each split into H heads of D/H), b_qkv [3D];
+ * W_o [D,D], b_o [D]; ln2 gamma, beta [D]; W_1 [D,F], b_1 [F]; W_2 [F,D], b_2 [D]
+ * -- 12D^2+13D per layer when F = 4D, the count behind Table 2. With an LM head:
+ * then final gamma, beta [D] and the tied embedding E [V,D]. Matrices are
+ * row-major [in, out]; y = x W + b. */
+typedef struct amdp_param_desc_t {
+    char     name[24];   /* e.g. "l0.w_qkv", "lnf_gamma", "embed" */
+    uint64_t offset;     /* elements from the start of the flat vector */
+    uint32_t rows, cols; /* vectors have rows = 1 */
+} amdp_param_desc_t;
+
+/* 0 if the configuration is invalid. Host only. */
+size_t amdp_stage_n_params(const amdp_stage_config_t* cfg);
+size_t amdp_stage_workspace_bytes(const amdp_stage_config_t* cfg);
+
+/* Describes the flat layout (host). AMDP_E_CAPACITY if cap is too small, with
+ * *n holding the number of entries. */
+int amdp_stage_param_layout(const amdp_stage_config_t* cfg, amdp_param_desc_t* descs, int32_t cap,
+                            int32_t* n);
+
+/* workspace: device, >= amdp_stage_workspace_bytes(cfg), 256-byte aligned.
+ * hip_stream: a hipStream_t (NULL = the null stream). The stage starts with
+ * all state zero and no published version: call amdp_stage_set_state next. */
+int amdp_stage_create(const amdp_stage_config_t* cfg, void* workspace, size_t workspace_bytes,
+                      void* hip_stream, amdp_stage_t** out);
+int amdp_stage_destroy(amdp_stage_t* stage);
+
+/* Loads master parameters and Adam moments (device, fp32, n_params each; m and
+ * v may be NULL = zeros), sets the step counter and the current version number,
+ * publishes that version in the stage's number type (round to nearest even for
+ * bf16), clears the gradient sum, the stash and all in-flight minibatches. */
+int amdp_stage_set_state(amdp_stage_t* stage, const float* theta, const float* m, const float* v,
+                         uint64_t step, uint32_t version);
+
+/* Copies state out. theta, m, v, G: device fp32 [n_params], each may be NULL.
+ * step, version: host, may be NULL. Copies are enqueued on the stage's stream. */
+int amdp_stage_get_state(amdp_stage_t* stage, float* theta, float* m, float* v, float* G,
+                         uint64_t* step, uint32_t* version);
+
+/* Copies the staged gradient of the last backward (device fp32 [n_params]);
+ * AMDP_E_MB_STATE when nothing is staged. */
+int amdp_stage_get_staged_grad(amdp_stage_t* stage, float* g);
+
+/* Number of resident versions and their numbers (host; versions may be NULL). */
+int amdp_stage_resident_versions(amdp_stage_t* stage, uint32_t* versions, int32_t cap, int32_t* n);
+
+/* Forward of minibatch `mb` with weight version `version` (Section 3.1: the
+ * version is whatever the schedule assigns; it must be resident).
+ *   X    device [N, D] token-major (row = sequence*s + position), stage dtype
+ *   aux  device int32: valid_len[b] for the BERT block (keys at positions >=
+ *        valid_len are masked), targets[N] on an LM-head stage, else NULL
+ *   out  device: Y [N, D] in the stage dtype, or one fp32 (the mean
+ *        cross-entropy) on an LM-head stage
+ * Saves the activations backward needs in a free activation slot and pins
+ * `version` until the minibatch's backward. */
+int amdp_stage_forward(amdp_stage_t* stage, int32_t mb, uint32_t version, const void* X,
+                       const int32_t* aux, void* out);
+
+/* Backward of minibatch `mb`. Activations are the ones its forward saved; every
+ * parameter value that enters (transposed weights, LayerNorm gains, the tied
+ * embedding) is read from `version`, which may differ from the forward's.
+ *   dY  device [N, D] stage dtype; NULL on an LM-head stage (seed d loss = 1)
+ *   dX  device [N, D] stage dtype; may be NULL (not written)
+ * Writes the minibatch's parameter gradient (fp32, flat layout) to the staging
+ * buffer; it stays there until amdp_grad_accumulate(mb). Unpins the forward's
+ * version. */
+int amdp_stage_backward(amdp_stage_t* stage, int32_t mb, uint32_t version, const void* dY, void* dX);
+
+/* G <- G + g_mb over the flat buffer (Section 3.3); frees the staging buffer
+ * and the minibatch's activation slot. */
+int amdp_grad_accumulate(amdp_stage_t* stage, int32_t mb);
+
+typedef struct amdp_adam_t {
+    uint32_t struct_size;
+    float lr, beta1, beta2, eps;
+    float weight_decay;     /* decoupled (AdamW); 0 in all benchmark configurations */
+    float grad_scale;       /* the update consumes grad_scale * G, e.g. 1/T */
+    int32_t bias_correction; /* 1: divide moments by (1 - beta^t); 0: the form printed in Appendix B.1 */
+} amdp_adam_t;
+
+/* One Adam step over the flat fp32 master parameters with the accumulated
+ * gradient (Section 3.3, Appendix B.1): m, v, theta updated in place, the new
+ * version (current + 1) published into a free version slot in the stage dtype,
+ * G cleared. *new_version (host, may be NULL) receives its number. Older
+ * versions stay resident while an in-flight minibatch's forward has read them. */
+int amdp_apply_update(amdp_stage_t* stage, const amdp_adam_t* hp, uint32_t* new_version);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AMDP_H */

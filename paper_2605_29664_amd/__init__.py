@@ -1,0 +1,15 @@
+"""MI355X-native AMDP pipeline-stage library: thin Python binding over the
+C ABI declared in include/amdp.h. Everything numerical runs in the HIP
+kernels of libamdp.so; this package only marshals arguments. PyTorch is used
+by callers for device memory and streams, never for arithmetic."""
+from .binding import (  # noqa: F401
+    AmdpError, lib, lib_path, build,
+    amdp_event_t, amdp_sched_params_t, amdp_sched_stats_t, amdp_stage_config_t,
+    amdp_param_desc_t, amdp_adam_t,
+    amdp_strerror, amdp_schedule_generate, amdp_schedule_stats, amdp_stage_map,
+    amdp_stage_n_params, amdp_stage_workspace_bytes, amdp_stage_param_layout,
+    Stage,
+    EV_F, EV_B, EV_A, EV_U, U_NEXT_BUBBLE, U_EAGER, BWD_STASHED, BWD_CURRENT,
+    FLAG_LAST_USE, FLAG_PARTIAL_WINDOW, BLOCK_GPT, BLOCK_BERT, FP32, BF16,
+    E_INVAL, E_MB_STATE, E_NO_SLOT, E_VERSION, E_STASH_FULL, E_HIP, E_CAPACITY,
+)

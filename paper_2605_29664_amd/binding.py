@@ -1,0 +1,276 @@
+"""ctypes binding of include/amdp.h. Function names and argument order follow
+the header; the only additions are error-code-to-exception translation and the
+`Stage` convenience wrapper that owns the workspace tensor."""
+import ctypes as C
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+_LIB_NAME = "libamdp.so"
+
+EV_F, EV_B, EV_A, EV_U = 0, 1, 2, 3
+U_NEXT_BUBBLE, U_EAGER = 0, 1
+BWD_STASHED, BWD_CURRENT = 0, 1
+FLAG_LAST_USE, FLAG_PARTIAL_WINDOW = 1, 2
+BLOCK_GPT, BLOCK_BERT = 0, 1
+FP32, BF16 = 0, 1
+E_INVAL, E_MB_STATE, E_NO_SLOT, E_VERSION, E_STASH_FULL, E_HIP, E_CAPACITY = -1, -2, -3, -4, -5, -6, -7
+
+
+class AmdpError(RuntimeError):
+    def __init__(self, code, what=""):
+        self.code = code
+        super().__init__(f"{what}: {amdp_strerror(code)} ({code})")
+
+
+class amdp_event_t(C.Structure):
+    _fields_ = [("kind", C.c_uint8), ("pipeline", C.c_uint8), ("flags", C.c_uint16),
+                ("mb", C.c_int32), ("version", C.c_uint32)]
+
+
+class amdp_sched_params_t(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("depth", C.c_int32), ("pipelines", C.c_int32),
+                ("stage", C.c_int32), ("inject_limit", C.c_int32), ("threshold", C.c_int32),
+                ("n_minibatches", C.c_int32), ("update_placement", C.c_int32),
+                ("bwd_version", C.c_int32)]
+
+
+class amdp_sched_stats_t(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("max_inflight", C.c_int32),
+                ("max_inflight_per_pipeline", C.c_int32), ("max_mismatch", C.c_int32),
+                ("max_affected_per_window", C.c_int32), ("max_live_versions", C.c_int32)]
+
+
+class amdp_stage_config_t(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("block_kind", C.c_int32), ("n_layers", C.c_int32),
+                ("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ffn", C.c_int32),
+                ("seq_len", C.c_int32), ("microbatch", C.c_int32), ("dtype", C.c_int32),
+                ("has_lm_head", C.c_int32), ("vocab", C.c_int32), ("ln_eps", C.c_float),
+                ("act_slots", C.c_int32), ("stash_slots", C.c_int32)]
+
+
+class amdp_param_desc_t(C.Structure):
+    _fields_ = [("name", C.c_char * 24), ("offset", C.c_uint64), ("rows", C.c_uint32),
+                ("cols", C.c_uint32)]
+
+
+class amdp_adam_t(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("lr", C.c_float), ("beta1", C.c_float),
+                ("beta2", C.c_float), ("eps", C.c_float), ("weight_decay", C.c_float),
+                ("grad_scale", C.c_float), ("bias_correction", C.c_int32)]
+
+
+def lib_path():
+    return os.path.join(HERE, _LIB_NAME)
+
+
+def build(verbose=False):
+    """Compile libamdp.so for gfx950 with hipcc (cross-compiles without a GPU)."""
+    src = [os.path.join(HERE, "csrc", "stage.hip"), os.path.join(HERE, "csrc", "schedule.cpp")]
+    cmd = ["hipcc", "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Wno-pass-failed", "-I" + os.path.join(ROOT, "include"), "-o", lib_path()] + src
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or res.returncode:
+        print(" ".join(cmd))
+        print(res.stdout, res.stderr)
+    if res.returncode:
+        raise RuntimeError("hipcc failed building libamdp.so")
+    global _lib
+    _lib = None
+    return lib_path()
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library. Fails loudly when it has not been built: there is no
+    fallback path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    L = C.CDLL(path)
+    vp, sz, i32, u32, u64 = C.c_void_p, C.c_size_t, C.c_int32, C.c_uint32, C.c_uint64
+    P = C.POINTER
+    sigs = {
+        "amdp_strerror": (C.c_char_p, [C.c_int]),
+        "amdp_schedule_generate": (C.c_int, [P(amdp_sched_params_t), P(amdp_event_t), sz, P(sz)]),
+        "amdp_schedule_stats": (C.c_int, [P(amdp_event_t), sz, i32, P(amdp_sched_stats_t)]),
+        "amdp_stage_map": (C.c_int, [i32, i32, i32, P(i32)]),
+        "amdp_stage_n_params": (sz, [P(amdp_stage_config_t)]),
+        "amdp_stage_workspace_bytes": (sz, [P(amdp_stage_config_t)]),
+        "amdp_stage_param_layout": (C.c_int, [P(amdp_stage_config_t), P(amdp_param_desc_t), i32, P(i32)]),
+        "amdp_stage_create": (C.c_int, [P(amdp_stage_config_t), vp, sz, vp, P(vp)]),
+        "amdp_stage_destroy": (C.c_int, [vp]),
+        "amdp_stage_set_state": (C.c_int, [vp, vp, vp, vp, u64, u32]),
+        "amdp_stage_get_state": (C.c_int, [vp, vp, vp, vp, vp, P(u64), P(u32)]),
+        "amdp_stage_get_staged_grad": (C.c_int, [vp, vp]),
+        "amdp_stage_resident_versions": (C.c_int, [vp, P(u32), i32, P(i32)]),
+        "amdp_stage_forward": (C.c_int, [vp, i32, u32, vp, vp, vp]),
+        "amdp_stage_backward": (C.c_int, [vp, i32, u32, vp, vp]),
+        "amdp_grad_accumulate": (C.c_int, [vp, i32]),
+        "amdp_apply_update": (C.c_int, [vp, P(amdp_adam_t), P(u32)]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(L, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = L
+    return L
+
+
+EXPORTED = ["amdp_strerror", "amdp_schedule_generate", "amdp_schedule_stats", "amdp_stage_map",
+            "amdp_stage_n_params", "amdp_stage_workspace_bytes", "amdp_stage_param_layout",
+            "amdp_stage_create", "amdp_stage_destroy", "amdp_stage_set_state", "amdp_stage_get_state",
+            "amdp_stage_get_staged_grad", "amdp_stage_resident_versions", "amdp_stage_forward",
+            "amdp_stage_backward", "amdp_grad_accumulate", "amdp_apply_update"]
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise AmdpError(rc, what)
+
+
+def amdp_strerror(code):
+    return lib().amdp_strerror(code).decode()
+
+
+def amdp_schedule_generate(depth, pipelines, stage, threshold, n_minibatches, inject_limit=2,
+                           update_placement=U_NEXT_BUBBLE, bwd_version=BWD_STASHED):
+    """Returns a ctypes array of amdp_event_t."""
+    p = amdp_sched_params_t(C.sizeof(amdp_sched_params_t), depth, pipelines, stage, inject_limit,
+                            threshold, n_minibatches, update_placement, bwd_version)
+    n = C.c_size_t(0)
+    rc = lib().amdp_schedule_generate(C.byref(p), None, 0, C.byref(n))
+    if rc not in (0, E_CAPACITY):
+        raise AmdpError(rc, "amdp_schedule_generate")
+    arr = (amdp_event_t * max(1, n.value))()
+    _check(lib().amdp_schedule_generate(C.byref(p), arr, n.value, C.byref(n)), "amdp_schedule_generate")
+    return (amdp_event_t * n.value).from_buffer(arr) if n.value else (amdp_event_t * 0)()
+
+
+def amdp_schedule_stats(events, threshold):
+    out = amdp_sched_stats_t(C.sizeof(amdp_sched_stats_t))
+    _check(lib().amdp_schedule_stats(events, len(events), threshold, C.byref(out)), "amdp_schedule_stats")
+    return {k: getattr(out, k) for k, _ in amdp_sched_stats_t._fields_[1:]}
+
+
+def amdp_stage_map(depth, pipeline, stage):
+    g = C.c_int32(-1)
+    _check(lib().amdp_stage_map(depth, pipeline, stage, C.byref(g)), "amdp_stage_map")
+    return g.value
+
+
+def make_config(block_kind, n_layers, d_model, n_heads, d_ffn, seq_len, microbatch, dtype,
+                has_lm_head=False, vocab=0, ln_eps=1e-5, act_slots=4, stash_slots=1):
+    return amdp_stage_config_t(C.sizeof(amdp_stage_config_t), block_kind, n_layers, d_model, n_heads,
+                               d_ffn, seq_len, microbatch, dtype, int(bool(has_lm_head)), vocab, ln_eps,
+                               act_slots, stash_slots)
+
+
+def amdp_stage_n_params(cfg):
+    return lib().amdp_stage_n_params(C.byref(cfg))
+
+
+def amdp_stage_workspace_bytes(cfg):
+    return lib().amdp_stage_workspace_bytes(C.byref(cfg))
+
+
+def amdp_stage_param_layout(cfg):
+    """List of (name, offset, rows, cols)."""
+    n = C.c_int32(0)
+    rc = lib().amdp_stage_param_layout(C.byref(cfg), None, 0, C.byref(n))
+    if rc not in (0, E_CAPACITY):
+        raise AmdpError(rc, "amdp_stage_param_layout")
+    arr = (amdp_param_desc_t * n.value)()
+    _check(lib().amdp_stage_param_layout(C.byref(cfg), arr, n.value, C.byref(n)), "amdp_stage_param_layout")
+    return [(d.name.decode(), int(d.offset), int(d.rows), int(d.cols)) for d in arr]
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    return C.c_void_p(t.data_ptr())
+
+
+class Stage:
+    """Owns the workspace tensor and the amdp_stage_t handle. Methods carry the
+    names of the C entry points they call. Tensors must live on the stage's
+    device; nothing here synchronises."""
+
+    def __init__(self, cfg, device="cuda:0", stream=None):
+        import torch
+        self.torch = torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        self.n_params = amdp_stage_n_params(cfg)
+        nbytes = amdp_stage_workspace_bytes(cfg)
+        if self.n_params == 0 or nbytes == 0:
+            raise AmdpError(E_INVAL, "amdp_stage_workspace_bytes")
+        self.workspace_bytes = nbytes
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        with torch.cuda.device(self.device):
+            self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+            base = self.workspace.data_ptr()
+            self._ws_ptr = (base + 255) // 256 * 256
+            h = C.c_void_p()
+            _check(lib().amdp_stage_create(C.byref(cfg), C.c_void_p(self._ws_ptr), nbytes,
+                                           C.c_void_p(self.stream.cuda_stream), C.byref(h)),
+                   "amdp_stage_create")
+        self.handle = h
+        self.act_dtype = torch.bfloat16 if cfg.dtype == BF16 else torch.float32
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib().amdp_stage_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def amdp_stage_set_state(self, theta, m=None, v=None, step=0, version=0):
+        _check(lib().amdp_stage_set_state(self.handle, _ptr(theta), _ptr(m), _ptr(v), step, version),
+               "amdp_stage_set_state")
+
+    def amdp_stage_get_state(self, theta=None, m=None, v=None, G=None):
+        step, ver = C.c_uint64(0), C.c_uint32(0)
+        _check(lib().amdp_stage_get_state(self.handle, _ptr(theta), _ptr(m), _ptr(v), _ptr(G),
+                                          C.byref(step), C.byref(ver)), "amdp_stage_get_state")
+        return step.value, ver.value
+
+    def amdp_stage_get_staged_grad(self, g):
+        _check(lib().amdp_stage_get_staged_grad(self.handle, _ptr(g)), "amdp_stage_get_staged_grad")
+
+    def amdp_stage_resident_versions(self):
+        arr = (C.c_uint32 * 32)()
+        n = C.c_int32(0)
+        _check(lib().amdp_stage_resident_versions(self.handle, arr, 32, C.byref(n)),
+               "amdp_stage_resident_versions")
+        return sorted(arr[i] for i in range(n.value))
+
+    def amdp_stage_forward(self, mb, version, X, aux, out):
+        _check(lib().amdp_stage_forward(self.handle, mb, version, _ptr(X), _ptr(aux), _ptr(out)),
+               "amdp_stage_forward")
+
+    def amdp_stage_backward(self, mb, version, dY, dX):
+        _check(lib().amdp_stage_backward(self.handle, mb, version, _ptr(dY), _ptr(dX)),
+               "amdp_stage_backward")
+
+    def amdp_grad_accumulate(self, mb):
+        _check(lib().amdp_grad_accumulate(self.handle, mb), "amdp_grad_accumulate")
+
+    def amdp_apply_update(self, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, grad_scale=1.0,
+                          bias_correction=True):
+        hp = amdp_adam_t(C.sizeof(amdp_adam_t), lr, beta1, beta2, eps, weight_decay, grad_scale,
+                         int(bool(bias_correction)))
+        nv = C.c_uint32(0)
+        _check(lib().amdp_apply_update(self.handle, C.byref(hp), C.byref(nv)), "amdp_apply_update")
+        return nv.value

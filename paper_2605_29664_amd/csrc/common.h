@@ -1,0 +1,125 @@
+// Shared device-side types and small helpers for the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace amdp {
+
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int WAVE = 64;
+
+template <class T> __device__ __forceinline__ float to_f32(T v) { return (float)v; }
+template <class T> __device__ __forceinline__ T from_f32(float v) { return (T)v; }   // bf16: RNE
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+    return v;
+}
+
+// Exact (erf) GELU and its derivative, fp32.
+__device__ __forceinline__ float gelu_f(float u) {
+    return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f));
+}
+__device__ __forceinline__ float gelu_grad_f(float u) {
+    const float cdf = 0.5f * (1.0f + erff(u * 0.70710678118654752f));
+    const float pdf = 0.39894228040143268f * __expf(-0.5f * u * u);
+    return cdf + u * pdf;
+}
+
+// Epilogue applied to every GEMM output element, in this order:
+//   v = alpha*acc (+ bias[n]) (* gelu'(gelu_u[m,n])) (+ res[m,n]);  C[m,n] = v
+//   (aux_out[m,n] = gelu(v) when aux_out is set)
+struct Epilogue {
+    const void* bias = nullptr;     // stage dtype [N]
+    const void* res = nullptr;      // stage dtype [M, ldr]
+    const void* gelu_u = nullptr;   // stage dtype [M, ldu]
+    void* aux_out = nullptr;        // stage dtype [M, ldc]
+    long ldr = 0, ldu = 0;
+    float alpha = 1.0f;
+    int out_f32 = 0;                // C is float instead of the stage dtype
+};
+
+template <class T>
+__device__ __forceinline__ void epilogue_store(const Epilogue& e, void* C, long ldc, long m, long n,
+                                               float acc) {
+    float v = acc * e.alpha;
+    if (e.bias) v += to_f32(((const T*)e.bias)[n]);
+    if (e.gelu_u) v *= gelu_grad_f(to_f32(((const T*)e.gelu_u)[m * e.ldu + n]));
+    if (e.res) v += to_f32(((const T*)e.res)[m * e.ldr + n]);
+    if (e.out_f32) ((float*)C)[m * ldc + n] = v;
+    else ((T*)C)[m * ldc + n] = from_f32<T>(v);
+    if (e.aux_out) ((T*)e.aux_out)[m * ldc + n] = from_f32<T>(gelu_f(v));
+}
+
+// Same epilogue for 8 consecutive columns n..n+7 of row m (bf16 stage dtype);
+// every pointer involved is 16-byte aligned at these columns.
+__device__ __forceinline__ void epilogue_store8(const Epilogue& e, void* C, long ldc, long m, long n,
+                                                float (&v)[8]) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] *= e.alpha;
+    if (e.bias) {
+        const bf16x8 b = *(const bf16x8*)((const bf16*)e.bias + n);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] += (float)b[k];
+    }
+    if (e.gelu_u) {
+        const bf16x8 u = *(const bf16x8*)((const bf16*)e.gelu_u + m * e.ldu + n);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] *= gelu_grad_f((float)u[k]);
+    }
+    if (e.res) {
+        const bf16x8 r = *(const bf16x8*)((const bf16*)e.res + m * e.ldr + n);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] += (float)r[k];
+    }
+    if (e.out_f32) {
+        float* p = (float*)C + m * ldc + n;
+        f32x4 lo = {v[0], v[1], v[2], v[3]}, hi = {v[4], v[5], v[6], v[7]};
+        *(f32x4*)p = lo;
+        *(f32x4*)(p + 4) = hi;
+    } else {
+        bf16x8 o;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) o[k] = (bf16)v[k];
+        *(bf16x8*)((bf16*)C + m * ldc + n) = o;
+    }
+    if (e.aux_out) {
+        bf16x8 o;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) o[k] = (bf16)gelu_f(v[k]);
+        *(bf16x8*)((bf16*)e.aux_out + m * ldc + n) = o;
+    }
+}
+
+// One GEMM problem, possibly batched over (outer, inner) = (sequence, head).
+//   C[m,n] = sum_k A(m,k) * B(k,n)
+//   A(m,k) = A[m*a_rs + k*a_cs], B(k,n) = B[k*b_rs + n*b_cs]   (element strides)
+// causal: 0 none;
+//   1 output tiles entirely above the diagonal (n > m) are not computed/written;
+//   2 contraction limited to k <= m (row block's upper bound);
+//   3 contraction limited to k >= m (row block's lower bound).
+struct GemmArgs {
+    const void* A; const void* B; void* C;
+    int M, N, K;
+    long a_rs, a_cs, b_rs, b_cs, ldc;
+    int batch = 1, batch_inner = 1;
+    long a_bo = 0, a_bi = 0, b_bo = 0, b_bi = 0, c_bo = 0, c_bi = 0;
+    int causal = 0;
+    Epilogue epi;
+};
+
+}  // namespace amdp

@@ -1,0 +1,309 @@
+// Row-wise kernels: LayerNorm forward/backward, masked softmax forward/backward,
+// cross-entropy, and the column reductions that produce bias and LayerNorm
+// parameter gradients. One 64-lane wavefront owns one row; reductions are
+// wave shuffles, statistics and exponentials are fp32, accesses are 16-byte
+// vectors along the row. No float atomics: results are run-to-run identical.
+#pragma once
+#include "common.h"
+
+namespace amdp {
+
+template <class T> struct Vec;
+template <> struct Vec<float> { static constexpr int N = 4; };
+template <> struct Vec<bf16> { static constexpr int N = 8; };
+
+template <class T>
+__device__ __forceinline__ void load_vec(const T* p, float (&out)[Vec<T>::N]) {
+    if constexpr (sizeof(T) == 4) {
+        f32x4 v = *(const f32x4*)p;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[i] = v[i];
+    } else {
+        bf16x8 v = *(const bf16x8*)p;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = (float)v[i];
+    }
+}
+template <class T>
+__device__ __forceinline__ void store_vec(T* p, const float (&in)[Vec<T>::N]) {
+    if constexpr (sizeof(T) == 4) {
+        f32x4 v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = in[i];
+        *(f32x4*)p = v;
+    } else {
+        bf16x8 v;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = (bf16)in[i];
+        *(bf16x8*)p = v;
+    }
+}
+
+constexpr int ROWS_PER_BLOCK = 4;   // 256 threads
+
+// ------------------------------------------------------------------ LayerNorm
+// y = (x - mean) * rstd * gamma + beta, biased variance; stats[2r] = mean, stats[2r+1] = rstd.
+template <class T>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+                                                     const T* __restrict__ beta, T* __restrict__ y,
+                                                     float* __restrict__ stats, int N, int D, float eps) {
+    constexpr int V = Vec<T>::N;
+    const int lane = threadIdx.x & 63;
+    const long row = (long)blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+    if (row >= N) return;
+    const T* xr = x + row * D;
+    const int nv = D / V;
+    float s = 0.f;
+    for (int c = lane; c < nv; c += WAVE) {
+        float a[V];
+        load_vec<T>(xr + c * V, a);
+#pragma unroll
+        for (int i = 0; i < V; ++i) s += a[i];
+    }
+    const float mean = wave_sum(s) / (float)D;
+    float q = 0.f;
+    for (int c = lane; c < nv; c += WAVE) {
+        float a[V];
+        load_vec<T>(xr + c * V, a);
+#pragma unroll
+        for (int i = 0; i < V; ++i) { const float d = a[i] - mean; q += d * d; }
+    }
+    const float rstd = rsqrtf(wave_sum(q) / (float)D + eps);
+    if (lane == 0) { stats[2 * row] = mean; stats[2 * row + 1] = rstd; }
+    T* yr = y + row * D;
+    for (int c = lane; c < nv; c += WAVE) {
+        float a[V], gm[V], bt[V];
+        load_vec<T>(xr + c * V, a);
+        load_vec<T>(gamma + c * V, gm);
+        load_vec<T>(beta + c * V, bt);
+#pragma unroll
+        for (int i = 0; i < V; ++i) a[i] = (a[i] - mean) * rstd * gm[i] + bt[i];
+        store_vec<T>(yr + c * V, a);
+    }
+}
+
+// dx = [res +] rstd * (dxhat - mean(dxhat) - xhat * mean(dxhat * xhat)), dxhat = dy * gamma
+template <class T>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                     const float* __restrict__ stats,
+                                                     const T* __restrict__ gamma, const T* res,
+                                                     T* dx, int N, int D) {
+    constexpr int V = Vec<T>::N;
+    const int lane = threadIdx.x & 63;
+    const long row = (long)blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+    if (row >= N) return;
+    const float mean = stats[2 * row], rstd = stats[2 * row + 1];
+    const T* xr = x + row * D;
+    const T* dyr = dy + row * D;
+    const int nv = D / V;
+    float s1 = 0.f, s2 = 0.f;
+    for (int c = lane; c < nv; c += WAVE) {
+        float a[V], d[V], gm[V];
+        load_vec<T>(xr + c * V, a);
+        load_vec<T>(dyr + c * V, d);
+        load_vec<T>(gamma + c * V, gm);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const float dxh = d[i] * gm[i];
+            s1 += dxh;
+            s2 += dxh * (a[i] - mean) * rstd;
+        }
+    }
+    const float c1 = wave_sum(s1) / (float)D, c2 = wave_sum(s2) / (float)D;
+    for (int c = lane; c < nv; c += WAVE) {
+        float a[V], d[V], gm[V], r[V];
+        load_vec<T>(xr + c * V, a);
+        load_vec<T>(dyr + c * V, d);
+        load_vec<T>(gamma + c * V, gm);
+        if (res) load_vec<T>(res + row * D + c * V, r);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const float xh = (a[i] - mean) * rstd;
+            float o = rstd * (d[i] * gm[i] - c1 - xh * c2);
+            if (res) o += r[i];
+            a[i] = o;
+        }
+        store_vec<T>(dx + row * D + c * V, a);
+    }
+}
+
+// ----------------------------------------------------------- column reductions
+// Stage 1: thread = column, block row = a chunk of rows.
+//   LN = false: partial[rc][c]      = sum_r dy[r][c]
+//   LN = true : partial[rc][c]      = sum_r dy[r][c] * xhat[r][c]      (dgamma)
+//               partial[rc][C + c]  = sum_r dy[r][c]                    (dbeta)
+template <class T, bool LN>
+__global__ __launch_bounds__(256) void colreduce_partial_kernel(const T* __restrict__ dy,
+                                                               const T* __restrict__ x,
+                                                               const float* __restrict__ stats,
+                                                               float* __restrict__ partial, int N, int C,
+                                                               int rows_per_chunk) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= C) return;
+    const int r0 = blockIdx.y * rows_per_chunk, r1 = min(N, r0 + rows_per_chunk);
+    float s = 0.f, sg = 0.f;
+    for (int r = r0; r < r1; ++r) {
+        const float d = to_f32(dy[(long)r * C + c]);
+        s += d;
+        if constexpr (LN) sg += d * (to_f32(x[(long)r * C + c]) - stats[2 * r]) * stats[2 * r + 1];
+    }
+    const long width = LN ? 2 * (long)C : C;
+    if constexpr (LN) {
+        partial[blockIdx.y * width + c] = sg;
+        partial[blockIdx.y * width + C + c] = s;
+    } else {
+        partial[blockIdx.y * width + c] = s;
+    }
+}
+// Stage 2: out[c] = sum over chunks, in chunk order.
+__global__ __launch_bounds__(256) void colreduce_final_kernel(const float* __restrict__ partial,
+                                                             float* __restrict__ out, int width, int chunks) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= width) return;
+    float s = 0.f;
+    for (int k = 0; k < chunks; ++k) s += partial[(long)k * width + c];
+    out[c] = s;
+}
+
+// -------------------------------------------------------------------- softmax
+// In place over rows of S [batch*s, s]: P = softmax(scale * S) over the visible
+// keys; hidden keys get probability exactly 0. Row r belongs to batch z = r / s,
+// query q = r % s, sequence z / H. causal: keys > q hidden. valid_len != null:
+// keys >= valid_len[sequence] hidden.
+template <class T>
+__global__ __launch_bounds__(256) void softmax_fwd_kernel(T* S, long rows, int s, float scale, int causal,
+                                                          const int32_t* __restrict__ valid_len, int H) {
+    constexpr int V = Vec<T>::N;
+    const int lane = threadIdx.x & 63;
+    const long row = (long)blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int q = (int)(row % s);
+    const long z = row / s;
+    int limit = s;
+    if (causal) limit = q + 1;
+    if (valid_len) limit = min(limit, max(0, valid_len[z / H]));
+    T* p = S + row * s;
+    const int nv = s / V;
+    float mx = -INFINITY;
+    for (int c = lane; c * V < limit; c += WAVE) {
+        float a[V];
+        load_vec<T>(p + c * V, a);
+#pragma unroll
+        for (int i = 0; i < V; ++i) if (c * V + i < limit) mx = fmaxf(mx, a[i]);
+    }
+    mx = wave_max(mx) * scale;
+    float sum = 0.f;
+    for (int c = lane; c * V < limit; c += WAVE) {
+        float a[V];
+        load_vec<T>(p + c * V, a);
+#pragma unroll
+        for (int i = 0; i < V; ++i) if (c * V + i < limit) sum += __expf(a[i] * scale - mx);
+    }
+    sum = wave_sum(sum);
+    const float inv = sum > 0.f ? 1.0f / sum : 0.f;
+    for (int c = lane; c < nv; c += WAVE) {
+        float a[V];
+        if (c * V < limit) load_vec<T>(p + c * V, a);
+#pragma unroll
+        for (int i = 0; i < V; ++i) a[i] = (c * V + i < limit) ? __expf(a[i] * scale - mx) * inv : 0.f;
+        store_vec<T>(p + c * V, a);
+    }
+}
+
+// In place on dP: dS = scale * P * (dP - sum_j dP_j P_j) over the visible keys, 0 elsewhere.
+template <class T>
+__global__ __launch_bounds__(256) void softmax_bwd_kernel(const T* __restrict__ P, T* dP, long rows, int s,
+                                                          float scale, int causal,
+                                                          const int32_t* __restrict__ valid_len, int H) {
+    constexpr int V = Vec<T>::N;
+    const int lane = threadIdx.x & 63;
+    const long row = (long)blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int q = (int)(row % s);
+    const long z = row / s;
+    int limit = s;
+    if (causal) limit = q + 1;
+    if (valid_len) limit = min(limit, max(0, valid_len[z / H]));
+    const T* p = P + row * s;
+    T* d = dP + row * s;
+    const int nv = s / V;
+    float dot = 0.f;
+    for (int c = lane; c * V < limit; c += WAVE) {
+        float a[V], b[V];
+        load_vec<T>(p + c * V, a);
+        load_vec<T>(d + c * V, b);
+#pragma unroll
+        for (int i = 0; i < V; ++i) if (c * V + i < limit) dot += a[i] * b[i];
+    }
+    dot = wave_sum(dot);
+    for (int c = lane; c < nv; c += WAVE) {
+        float a[V], b[V];
+        if (c * V < limit) { load_vec<T>(p + c * V, a); load_vec<T>(d + c * V, b); }
+#pragma unroll
+        for (int i = 0; i < V; ++i) a[i] = (c * V + i < limit) ? scale * a[i] * (b[i] - dot) : 0.f;
+        store_vec<T>(d + c * V, a);
+    }
+}
+
+// -------------------------------------------------------------- cross-entropy
+// Row n of logits [N, ld] (V valid columns): row_loss[n] = logsumexp - logit[target];
+// logits are overwritten with d loss / d logits = (softmax - onehot) / N, pad columns 0.
+template <class T>
+__global__ __launch_bounds__(256) void ce_fwd_kernel(T* logits, const int32_t* __restrict__ targets,
+                                                     float* __restrict__ row_loss, int N, int Vocab, long ld) {
+    constexpr int V = Vec<T>::N;
+    const int lane = threadIdx.x & 63;
+    const long row = (long)blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+    if (row >= N) return;
+    T* p = logits + row * ld;
+    const int nv = (int)(ld / V);
+    const int t = targets[row];
+    float mx = -INFINITY;
+    for (int c = lane; c * V < Vocab; c += WAVE) {
+        float a[V];
+        load_vec<T>(p + c * V, a);
+#pragma unroll
+        for (int i = 0; i < V; ++i) if (c * V + i < Vocab) mx = fmaxf(mx, a[i]);
+    }
+    mx = wave_max(mx);
+    float sum = 0.f, tl = 0.f;
+    for (int c = lane; c * V < Vocab; c += WAVE) {
+        float a[V];
+        load_vec<T>(p + c * V, a);
+#pragma unroll
+        for (int i = 0; i < V; ++i) if (c * V + i < Vocab) {
+            sum += __expf(a[i] - mx);
+            if (c * V + i == t) tl = a[i];
+        }
+    }
+    sum = wave_sum(sum);
+    tl = wave_sum(tl);
+    if (lane == 0) row_loss[row] = mx + __logf(sum) - tl;
+    const float inv = 1.0f / sum, invN = 1.0f / (float)N;
+    for (int c = lane; c < nv; c += WAVE) {
+        float a[V];
+        if (c * V < Vocab) load_vec<T>(p + c * V, a);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const int col = c * V + i;
+            a[i] = col < Vocab ? (__expf(a[i] - mx) * inv - (col == t ? 1.f : 0.f)) * invN : 0.f;
+        }
+        store_vec<T>(p + c * V, a);
+    }
+}
+
+// mean of row losses, one block, fixed order
+__global__ __launch_bounds__(256) void mean_kernel(const float* __restrict__ v, float* out, int N) {
+    __shared__ float sh[256];
+    float s = 0.f;
+    for (int i = threadIdx.x; i < N; i += 256) s += v[i];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = sh[0] / (float)N;
+}
+
+}  // namespace amdp

@@ -1,0 +1,784 @@
+// Stage executor: owns the layout of the caller's workspace (master
+// parameters, Adam moments, gradient sum and staging, weight-version slots,
+// activation slots, scratch), the residency rules for versions and in-flight
+// minibatches, and the order of kernel launches for forward, backward,
+// accumulate and update. Everything is enqueued on one HIP stream.
+#include "amdp.h"
+#include "common.h"
+#include "gemm_mfma.h"
+#include "gemm_simple.h"
+#include "rowwise.h"
+#include "streaming.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace amdp;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+constexpr int MAX_VSLOTS = 16;
+constexpr int MAX_ASLOTS = 64;
+constexpr int LM_PAD_ROWS = 256;   // vocabulary rows are padded to a multiple of this
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+enum Field { LN1_G, LN1_B, W_QKV, B_QKV, W_O, B_O, LN2_G, LN2_B, W_1, B_1, W_2, B_2, N_FIELDS };
+const char* const FIELD_NAMES[N_FIELDS] = {"ln1_gamma", "ln1_beta", "w_qkv", "b_qkv", "w_o", "b_o",
+                                           "ln2_gamma", "ln2_beta", "w_1",   "b_1",   "w_2", "b_2"};
+
+struct Dims {
+    int L, D, H, dh, F, s, b, N, V;
+    long Vld;
+    bool lm, bf, causal;
+    size_t esz;
+    long field_size(int f) const {
+        switch (f) {
+            case LN1_G: case LN1_B: case LN2_G: case LN2_B: case B_O: case B_2: return D;
+            case W_QKV: return 3L * D * D;
+            case B_QKV: return 3L * D;
+            case W_O: return (long)D * D;
+            case W_1: case W_2: return (long)D * F;
+            case B_1: return F;
+        }
+        return 0;
+    }
+    long layer_params() const {
+        long t = 0;
+        for (int f = 0; f < N_FIELDS; ++f) t += field_size(f);
+        return t;
+    }
+    long off(int layer, int f) const {
+        long t = layer * layer_params();
+        for (int k = 0; k < f; ++k) t += field_size(k);
+        return t;
+    }
+    long off_lnf() const { return L * layer_params(); }
+    long off_embed() const { return off_lnf() + 2L * D; }
+    long n_params() const { return lm ? off_embed() + (long)V * D : L * layer_params(); }
+    long n_alloc() const {
+        long n = n_params() + (lm ? (long)LM_PAD_ROWS * D : 0);
+        return (long)round_up((size_t)n, 1024);
+    }
+};
+
+bool make_dims(const amdp_stage_config_t* c, Dims* d) {
+    if (!c || c->struct_size != sizeof(amdp_stage_config_t)) return false;
+    if (c->block_kind != AMDP_BLOCK_GPT_PRELN_CAUSAL && c->block_kind != AMDP_BLOCK_BERT_POSTLN_BIDIR)
+        return false;
+    if (c->dtype != AMDP_FP32 && c->dtype != AMDP_BF16) return false;
+    if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->d_ffn < 1 || c->seq_len < 1 ||
+        c->microbatch < 1)
+        return false;
+    if (c->d_model % c->n_heads) return false;
+    if (c->has_lm_head && c->vocab < 1) return false;
+    if (c->act_slots < 1 || c->act_slots > MAX_ASLOTS) return false;
+    if (c->stash_slots < 1 || c->stash_slots + 1 > MAX_VSLOTS) return false;
+    if (!(c->ln_eps > 0.f)) return false;
+    const int vec = c->dtype == AMDP_BF16 ? 8 : 4;   // row kernels move 16-byte vectors
+    if (c->d_model % vec || c->d_ffn % vec || c->seq_len % vec) return false;
+    if ((long)c->seq_len * c->microbatch > (1L << 24)) return false;
+    d->L = c->n_layers; d->D = c->d_model; d->H = c->n_heads; d->dh = c->d_model / c->n_heads;
+    d->F = c->d_ffn; d->s = c->seq_len; d->b = c->microbatch; d->N = c->seq_len * c->microbatch;
+    d->lm = c->has_lm_head != 0; d->V = d->lm ? c->vocab : 0;
+    d->Vld = d->lm ? (long)round_up((size_t)d->V, LM_PAD_ROWS) : 0;
+    d->bf = c->dtype == AMDP_BF16; d->esz = d->bf ? 2 : 4;
+    d->causal = c->block_kind == AMDP_BLOCK_GPT_PRELN_CAUSAL;
+    return true;
+}
+
+// ---- workspace carving ------------------------------------------------------
+struct LayerAct {   // byte offsets inside an activation slot
+    size_t xin, a, qkv, P, o, y1, c, u, h, st1, st2;
+};
+struct SlotLayout {
+    std::vector<LayerAct> layers;
+    size_t yL = 0, z = 0, stf = 0, dlogits = 0;
+    size_t bytes = 0;
+};
+struct Carve {
+    size_t theta, m, v, G, g, versions, version_bytes, act, slot_bytes;
+    size_t buf[4], dqkv, dffn, dP, partial, row_loss, total;
+    int partial_chunks;
+    SlotLayout slot;
+};
+
+void carve(const Dims& d, const amdp_stage_config_t& c, Carve* w) {
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = round_up(off + bytes, ALIGN); return o; };
+    const size_t na = (size_t)d.n_alloc();
+    w->theta = take(na * 4); w->m = take(na * 4); w->v = take(na * 4); w->G = take(na * 4);
+    w->g = take(na * 4);
+    w->version_bytes = round_up(na * d.esz, ALIGN);
+    w->versions = take(w->version_bytes * (size_t)(c.stash_slots + 1));
+
+    const size_t ND = (size_t)d.N * d.D * d.esz, NF = (size_t)d.N * d.F * d.esz;
+    const size_t PP = (size_t)d.b * d.H * d.s * d.s * d.esz;
+    {
+        size_t so = 0;
+        auto st = [&](size_t bytes) { size_t o = so; so = round_up(so + bytes, ALIGN); return o; };
+        w->slot.layers.resize(d.L);
+        for (int l = 0; l < d.L; ++l) {
+            LayerAct& a = w->slot.layers[l];
+            a.xin = st(ND); a.a = st(ND); a.qkv = st(3 * ND); a.P = st(PP); a.o = st(ND);
+            a.y1 = st(ND); a.c = st(ND); a.u = st(NF); a.h = st(NF);
+            a.st1 = st((size_t)d.N * 8); a.st2 = st((size_t)d.N * 8);
+        }
+        if (d.lm) {
+            w->slot.yL = st(ND); w->slot.z = st(ND); w->slot.stf = st((size_t)d.N * 8);
+            w->slot.dlogits = st((size_t)d.N * d.Vld * d.esz);
+        }
+        w->slot.bytes = so;
+    }
+    w->slot_bytes = w->slot.bytes;
+    w->act = take(w->slot_bytes * (size_t)c.act_slots);
+    for (int i = 0; i < 4; ++i) w->buf[i] = take(ND);
+    w->dqkv = take(3 * ND);
+    w->dffn = take(NF);
+    w->dP = take(PP);
+    w->partial_chunks = 64;
+    const size_t maxw = (size_t)std::max(std::max(3 * d.D, d.F), 2 * d.D);
+    w->partial = take((size_t)w->partial_chunks * maxw * 4);
+    w->row_loss = take((size_t)d.N * 4);
+    w->total = off;
+}
+
+struct VSlot { bool valid = false; uint32_t version = 0; int pins = 0; };
+struct ASlot { bool used = false; int32_t mb = 0; int vslot = -1; bool backwarded = false; };
+
+}  // namespace
+
+struct amdp_stage {
+    amdp_stage_config_t cfg;
+    Dims d;
+    Carve w;
+    char* base;
+    hipStream_t stream;
+    VSlot vs[MAX_VSLOTS];
+    ASlot as[MAX_ASLOTS];
+    int n_vslots;
+    int cur_slot = -1;
+    uint32_t cur_version = 0;
+    uint64_t step = 0;
+    int staged_slot = -1;   // activation slot whose gradient sits in the staging buffer
+    bool use_tr = true;
+    int force_tile = 0;
+
+    template <class P = void> P* at(size_t off) const { return (P*)(base + off); }
+    char* version_ptr(int slot) const { return base + w.versions + (size_t)slot * w.version_bytes; }
+    char* act_ptr(int slot) const { return base + w.act + (size_t)slot * w.slot_bytes; }
+    int find_version(uint32_t v) const {
+        for (int i = 0; i < n_vslots; ++i) if (vs[i].valid && vs[i].version == v) return i;
+        return -1;
+    }
+    int find_mb(int32_t mb) const {
+        for (int i = 0; i < cfg.act_slots; ++i) if (as[i].used && as[i].mb == mb) return i;
+        return -1;
+    }
+    // a slot can be reused when it holds no version, or an old one no in-flight
+    // minibatch's forward has read
+    int free_vslot() const {
+        for (int i = 0; i < n_vslots; ++i) if (!vs[i].valid) return i;
+        for (int i = 0; i < n_vslots; ++i) if (i != cur_slot && vs[i].pins == 0) return i;
+        return -1;
+    }
+    void drop_unpinned() {
+        for (int i = 0; i < n_vslots; ++i)
+            if (vs[i].valid && i != cur_slot && vs[i].pins == 0) vs[i].valid = false;
+    }
+};
+
+namespace {
+
+#define HIP_TRY(expr) do { if ((expr) != hipSuccess) return AMDP_E_HIP; } while (0)
+#define TRY(expr) do { int rc_ = (expr); if (rc_ != AMDP_OK) return rc_; } while (0)
+
+inline int after_launch() { return hipGetLastError() == hipSuccess ? AMDP_OK : AMDP_E_HIP; }
+
+// ---- GEMM dispatch ----------------------------------------------------------
+template <bool A_KM, bool B_KM>
+int gemm_bf16_layout(amdp_stage* st, const GemmArgs& g) {
+    const long tiles256 = (long)(g.M / 256) * (g.N / 256) * g.batch;
+    const bool ok256 = mfma_shape_ok<256, 256>(g, A_KM, B_KM);
+    const bool ok128 = mfma_shape_ok<128, 128>(g, A_KM, B_KM);
+    const bool ok64 = mfma_shape_ok<128, 64>(g, A_KM, B_KM);
+    hipError_t e;
+    const bool tr = st->use_tr;
+    int tile = 0;
+    if (ok256 && (tiles256 >= 192 || !ok128)) tile = 256;
+    else if (ok128) tile = 128;
+    else if (ok64) tile = 64;
+    if (st->force_tile == 128 && ok128) tile = 128;
+    if (st->force_tile == 256 && ok256) tile = 256;
+    if (st->force_tile < 0) tile = 0;
+    switch (tile) {
+        case 256:
+            e = tr ? launch_gemm_mfma_inst<256, 256, A_KM, B_KM, true>(g, st->stream)
+                   : launch_gemm_mfma_inst<256, 256, A_KM, B_KM, false>(g, st->stream);
+            break;
+        case 128:
+            e = tr ? launch_gemm_mfma_inst<128, 128, A_KM, B_KM, true>(g, st->stream)
+                   : launch_gemm_mfma_inst<128, 128, A_KM, B_KM, false>(g, st->stream);
+            break;
+        case 64:
+            e = tr ? launch_gemm_mfma_inst<128, 64, A_KM, B_KM, true>(g, st->stream)
+                   : launch_gemm_mfma_inst<128, 64, A_KM, B_KM, false>(g, st->stream);
+            break;
+        default:
+            e = launch_gemm_simple<bf16>(g, st->stream);
+    }
+    return e == hipSuccess ? AMDP_OK : AMDP_E_HIP;
+}
+
+enum GemmLayout { G_NN, G_NT, G_TN };
+
+// lda/ldb are the leading dimensions of the operands AS STORED:
+//   NN: A [M,K] lda, B [K,N] ldb      NT: A [M,K], B [N,K]      TN: A [K,M], B [K,N]
+int gemm(amdp_stage* st, GemmLayout lay, GemmArgs g, long lda, long ldb) {
+    switch (lay) {
+        case G_NN: g.a_rs = lda; g.a_cs = 1; g.b_rs = ldb; g.b_cs = 1; break;
+        case G_NT: g.a_rs = lda; g.a_cs = 1; g.b_rs = 1; g.b_cs = ldb; break;
+        case G_TN: g.a_rs = 1; g.a_cs = lda; g.b_rs = ldb; g.b_cs = 1; break;
+    }
+    if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return AMDP_OK;
+    if (!st->d.bf) return launch_gemm_simple<float>(g, st->stream) == hipSuccess ? AMDP_OK : AMDP_E_HIP;
+    switch (lay) {
+        case G_NN: return gemm_bf16_layout<false, true>(st, g);
+        case G_NT: return gemm_bf16_layout<false, false>(st, g);
+        default: return gemm_bf16_layout<true, true>(st, g);
+    }
+}
+
+// ---- typed launch helpers ---------------------------------------------------
+template <class T>
+int ln_fwd(amdp_stage* st, const void* x, const void* gamma, const void* beta, void* y, float* stats) {
+    const Dims& d = st->d;
+    hipLaunchKernelGGL(ln_fwd_kernel<T>, dim3((d.N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0,
+                       st->stream, (const T*)x, (const T*)gamma, (const T*)beta, (T*)y, stats, d.N, d.D,
+                       st->cfg.ln_eps);
+    return after_launch();
+}
+template <class T>
+int ln_bwd(amdp_stage* st, const void* dy, const void* x, const float* stats, const void* gamma,
+           const void* res, void* dx) {
+    const Dims& d = st->d;
+    hipLaunchKernelGGL(ln_bwd_kernel<T>, dim3((d.N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0,
+                       st->stream, (const T*)dy, (const T*)x, stats, (const T*)gamma, (const T*)res, (T*)dx,
+                       d.N, d.D);
+    return after_launch();
+}
+// out[0..C) = column sums of dy [N, C]; with LN: out[0..C) = sum dy*xhat, out[C..2C) = sum dy
+template <class T, bool LN>
+int colreduce(amdp_stage* st, const void* dy, const void* x, const float* stats, float* out, int C) {
+    const Dims& d = st->d;
+    const int rpc = std::max(16, (d.N + st->w.partial_chunks - 1) / st->w.partial_chunks);
+    const int chunks = (d.N + rpc - 1) / rpc;
+    float* partial = st->at<float>(st->w.partial);
+    hipLaunchKernelGGL((colreduce_partial_kernel<T, LN>), dim3((C + 255) / 256, chunks), dim3(256), 0,
+                       st->stream, (const T*)dy, (const T*)x, stats, partial, d.N, C, rpc);
+    TRY(after_launch());
+    const int width = LN ? 2 * C : C;
+    hipLaunchKernelGGL(colreduce_final_kernel, dim3((width + 255) / 256), dim3(256), 0, st->stream, partial,
+                       out, width, chunks);
+    return after_launch();
+}
+
+GemmArgs attn_batch(const Dims& d) {
+    GemmArgs g{};
+    g.batch = d.b * d.H;
+    g.batch_inner = d.H;
+    return g;
+}
+
+template <class T>
+int attention_fwd(amdp_stage* st, const void* qkv_, void* P_, void* o_, const int32_t* valid) {
+    const Dims& d = st->d;
+    const T* qkv = (const T*)qkv_;
+    const long ld3 = 3L * d.D;
+    {   // S = Q K^T
+        GemmArgs g = attn_batch(d);
+        g.A = qkv; g.B = qkv + d.D; g.C = P_;
+        g.M = d.s; g.N = d.s; g.K = d.dh; g.ldc = d.s;
+        g.a_bo = (long)d.s * ld3; g.a_bi = d.dh; g.b_bo = g.a_bo; g.b_bi = d.dh;
+        g.c_bo = (long)d.H * d.s * d.s; g.c_bi = (long)d.s * d.s;
+        g.causal = d.causal ? 1 : 0;
+        TRY(gemm(st, G_NT, g, ld3, ld3));
+    }
+    const long rows = (long)d.b * d.H * d.s;
+    hipLaunchKernelGGL(softmax_fwd_kernel<T>, dim3((unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK)),
+                       dim3(256), 0, st->stream, (T*)P_, rows, d.s, 1.0f / sqrtf((float)d.dh),
+                       d.causal ? 1 : 0, valid, d.H);
+    TRY(after_launch());
+    {   // O = P V
+        GemmArgs g = attn_batch(d);
+        g.A = P_; g.B = qkv + 2 * d.D; g.C = o_;
+        g.M = d.s; g.N = d.dh; g.K = d.s; g.ldc = d.D;
+        g.a_bo = (long)d.H * d.s * d.s; g.a_bi = (long)d.s * d.s;
+        g.b_bo = (long)d.s * ld3; g.b_bi = d.dh;
+        g.c_bo = (long)d.s * d.D; g.c_bi = d.dh;
+        g.causal = d.causal ? 2 : 0;
+        TRY(gemm(st, G_NN, g, d.s, ld3));
+    }
+    return AMDP_OK;
+}
+
+// dqkv from d_out, the saved qkv and probabilities; dP is scratch [b*H, s, s]
+template <class T>
+int attention_bwd(amdp_stage* st, const void* dO_, const void* qkv_, const void* P_, void* dP_,
+                  void* dqkv_, const int32_t* valid) {
+    const Dims& d = st->d;
+    const T* qkv = (const T*)qkv_;
+    T* dqkv = (T*)dqkv_;
+    const long ld3 = 3L * d.D;
+    const long sP_o = (long)d.H * d.s * d.s, sP_i = (long)d.s * d.s;
+    const long sQ_o = (long)d.s * ld3, sQ_i = d.dh;
+    const long sO_o = (long)d.s * d.D, sO_i = d.dh;
+    {   // dV = P^T dO
+        GemmArgs g = attn_batch(d);
+        g.A = P_; g.B = dO_; g.C = dqkv + 2 * d.D;
+        g.M = d.s; g.N = d.dh; g.K = d.s; g.ldc = ld3;
+        g.a_bo = sP_o; g.a_bi = sP_i; g.b_bo = sO_o; g.b_bi = sO_i; g.c_bo = sQ_o; g.c_bi = sQ_i;
+        g.causal = d.causal ? 3 : 0;
+        TRY(gemm(st, G_TN, g, d.s, d.D));
+    }
+    {   // dP = dO V^T
+        GemmArgs g = attn_batch(d);
+        g.A = dO_; g.B = qkv + 2 * d.D; g.C = dP_;
+        g.M = d.s; g.N = d.s; g.K = d.dh; g.ldc = d.s;
+        g.a_bo = sO_o; g.a_bi = sO_i; g.b_bo = sQ_o; g.b_bi = sQ_i; g.c_bo = sP_o; g.c_bi = sP_i;
+        g.causal = d.causal ? 1 : 0;
+        TRY(gemm(st, G_NT, g, d.D, ld3));
+    }
+    const long rows = (long)d.b * d.H * d.s;
+    hipLaunchKernelGGL(softmax_bwd_kernel<T>, dim3((unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK)),
+                       dim3(256), 0, st->stream, (const T*)P_, (T*)dP_, rows, d.s, 1.0f / sqrtf((float)d.dh),
+                       d.causal ? 1 : 0, valid, d.H);
+    TRY(after_launch());
+    {   // dQ = dS K
+        GemmArgs g = attn_batch(d);
+        g.A = dP_; g.B = qkv + d.D; g.C = dqkv;
+        g.M = d.s; g.N = d.dh; g.K = d.s; g.ldc = ld3;
+        g.a_bo = sP_o; g.a_bi = sP_i; g.b_bo = sQ_o; g.b_bi = sQ_i; g.c_bo = sQ_o; g.c_bi = sQ_i;
+        g.causal = d.causal ? 2 : 0;
+        TRY(gemm(st, G_NN, g, d.s, ld3));
+    }
+    {   // dK = dS^T Q
+        GemmArgs g = attn_batch(d);
+        g.A = dP_; g.B = qkv; g.C = dqkv + d.D;
+        g.M = d.s; g.N = d.dh; g.K = d.s; g.ldc = ld3;
+        g.a_bo = sP_o; g.a_bi = sP_i; g.b_bo = sQ_o; g.b_bi = sQ_i; g.c_bo = sQ_o; g.c_bi = sQ_i;
+        g.causal = d.causal ? 3 : 0;
+        TRY(gemm(st, G_TN, g, d.s, ld3));
+    }
+    return AMDP_OK;
+}
+
+// Y[M,N] = X[M,K] W[K,N] (+bias) (+res) ; optional second output gelu(Y)
+int linear_fwd(amdp_stage* st, const void* X, const void* W, const void* bias, const void* res, void* Y,
+               void* gelu_out, int M, int N, int K) {
+    GemmArgs g{};
+    g.A = X; g.B = W; g.C = Y; g.M = M; g.N = N; g.K = K; g.ldc = N;
+    g.epi.bias = bias; g.epi.res = res; g.epi.ldr = N; g.epi.aux_out = gelu_out;
+    return gemm(st, G_NN, g, K, N);
+}
+// dX[M,K] = dY[M,N] W[K,N]^T (* gelu'(u)) (+res)
+int linear_dx(amdp_stage* st, const void* dY, const void* W, const void* gelu_u, const void* res, void* dX,
+              int M, int N, int K) {
+    GemmArgs g{};
+    g.A = dY; g.B = W; g.C = dX; g.M = M; g.N = K; g.K = N; g.ldc = K;
+    g.epi.gelu_u = gelu_u; g.epi.ldu = K; g.epi.res = res; g.epi.ldr = K;
+    return gemm(st, G_NT, g, N, N);
+}
+// dW[K,N] (fp32) = X[M,K]^T dY[M,N]
+int linear_dw(amdp_stage* st, const void* X, const void* dY, float* dW, int M, int N, int K) {
+    GemmArgs g{};
+    g.A = X; g.B = dY; g.C = dW; g.M = K; g.N = N; g.K = M; g.ldc = N;
+    g.epi.out_f32 = 1;
+    return gemm(st, G_TN, g, K, N);
+}
+
+template <class T>
+int forward_impl(amdp_stage* st, int aslot, int vslot, const void* X, const int32_t* aux, void* out) {
+    const Dims& d = st->d;
+    const T* W = (const T*)st->version_ptr(vslot);
+    char* S = st->act_ptr(aslot);
+    const size_t ND = (size_t)d.N * d.D * sizeof(T);
+    // aux is the padding mask for bidirectional blocks, the targets on an LM-head stage
+    const int32_t* valid = (!d.causal && !d.lm) ? aux : nullptr;
+    HIP_TRY(hipMemcpyAsync(S + st->w.slot.layers[0].xin, X, ND, hipMemcpyDeviceToDevice, st->stream));
+    for (int l = 0; l < d.L; ++l) {
+        const LayerAct& a = st->w.slot.layers[l];
+        void* xin = S + a.xin;
+        void* yout = (l + 1 < d.L) ? (void*)(S + st->w.slot.layers[l + 1].xin)
+                                   : (d.lm ? (void*)(S + st->w.slot.yL) : out);
+        auto P = [&](int f) { return (const void*)(W + d.off(l, f)); };
+        if (d.causal) {
+            TRY(ln_fwd<T>(st, xin, P(LN1_G), P(LN1_B), S + a.a, (float*)(S + a.st1)));
+            TRY(linear_fwd(st, S + a.a, P(W_QKV), P(B_QKV), nullptr, S + a.qkv, nullptr, d.N, 3 * d.D, d.D));
+            TRY(attention_fwd<T>(st, S + a.qkv, S + a.P, S + a.o, valid));
+            TRY(linear_fwd(st, S + a.o, P(W_O), P(B_O), xin, S + a.y1, nullptr, d.N, d.D, d.D));
+            TRY(ln_fwd<T>(st, S + a.y1, P(LN2_G), P(LN2_B), S + a.c, (float*)(S + a.st2)));
+            TRY(linear_fwd(st, S + a.c, P(W_1), P(B_1), nullptr, S + a.u, S + a.h, d.N, d.F, d.D));
+            TRY(linear_fwd(st, S + a.h, P(W_2), P(B_2), S + a.y1, yout, nullptr, d.N, d.D, d.F));
+        } else {
+            // post-LN: field `a` holds the pre-norm sum after attention, `c` the one after the MLP
+            TRY(linear_fwd(st, xin, P(W_QKV), P(B_QKV), nullptr, S + a.qkv, nullptr, d.N, 3 * d.D, d.D));
+            TRY(attention_fwd<T>(st, S + a.qkv, S + a.P, S + a.o, valid));
+            TRY(linear_fwd(st, S + a.o, P(W_O), P(B_O), xin, S + a.a, nullptr, d.N, d.D, d.D));
+            TRY(ln_fwd<T>(st, S + a.a, P(LN1_G), P(LN1_B), S + a.y1, (float*)(S + a.st1)));
+            TRY(linear_fwd(st, S + a.y1, P(W_1), P(B_1), nullptr, S + a.u, S + a.h, d.N, d.F, d.D));
+            TRY(linear_fwd(st, S + a.h, P(W_2), P(B_2), S + a.y1, S + a.c, nullptr, d.N, d.D, d.F));
+            TRY(ln_fwd<T>(st, S + a.c, P(LN2_G), P(LN2_B), yout, (float*)(S + a.st2)));
+        }
+    }
+    if (d.lm) {
+        const SlotLayout& sl = st->w.slot;
+        TRY(ln_fwd<T>(st, S + sl.yL, W + d.off_lnf(), W + d.off_lnf() + d.D, S + sl.z, (float*)(S + sl.stf)));
+        GemmArgs g{};   // logits = z E^T ; pad rows of E are zero in every version slot
+        g.A = S + sl.z; g.B = W + d.off_embed(); g.C = S + sl.dlogits;
+        g.M = d.N; g.N = (int)d.Vld; g.K = d.D; g.ldc = d.Vld;
+        TRY(gemm(st, G_NT, g, d.D, d.D));
+        float* row_loss = st->at<float>(st->w.row_loss);
+        hipLaunchKernelGGL(ce_fwd_kernel<T>, dim3((d.N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0,
+                           st->stream, (T*)(S + sl.dlogits), aux, row_loss, d.N, d.V, d.Vld);
+        TRY(after_launch());
+        hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(256), 0, st->stream, row_loss, (float*)out, d.N);
+        TRY(after_launch());
+    }
+    return AMDP_OK;
+}
+
+template <class T>
+int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, const void* dY, void* dX) {
+    const Dims& d = st->d;
+    const T* W = (const T*)st->version_ptr(vslot);
+    char* S = st->act_ptr(aslot);
+    float* g = st->at<float>(st->w.g);
+    void* buf[4] = {st->at<>(st->w.buf[0]), st->at<>(st->w.buf[1]), st->at<>(st->w.buf[2]),
+                    st->at<>(st->w.buf[3])};
+    void* dqkv = st->at<>(st->w.dqkv);
+    void* dffn = st->at<>(st->w.dffn);
+    void* dP = st->at<>(st->w.dP);
+
+    const void* dcur = dY;
+    int cur_idx = -1;   // index of the buffer dcur lives in, -1 = caller's
+    if (d.lm) {
+        const SlotLayout& sl = st->w.slot;
+        {   // dE = dlogits^T z   (rows >= V are zero and land in the padding)
+            GemmArgs a{};
+            a.A = S + sl.dlogits; a.B = S + sl.z; a.C = g + d.off_embed();
+            a.M = (int)d.Vld; a.N = d.D; a.K = d.N; a.ldc = d.D; a.epi.out_f32 = 1;
+            TRY(gemm(st, G_TN, a, d.Vld, d.D));
+        }
+        {   // dz = dlogits E
+            GemmArgs a{};
+            a.A = S + sl.dlogits; a.B = W + d.off_embed(); a.C = buf[1];
+            a.M = d.N; a.N = d.D; a.K = (int)d.Vld; a.ldc = d.D;
+            TRY(gemm(st, G_NN, a, d.Vld, d.D));
+        }
+        TRY((colreduce<T, true>(st, buf[1], S + sl.yL, (const float*)(S + sl.stf), g + d.off_lnf(), d.D)));
+        TRY(ln_bwd<T>(st, buf[1], S + sl.yL, (const float*)(S + sl.stf), W + d.off_lnf(), nullptr, buf[0]));
+        dcur = buf[0];
+        cur_idx = 0;
+    }
+
+    for (int l = d.L - 1; l >= 0; --l) {
+        const LayerAct& a = st->w.slot.layers[l];
+        auto P = [&](int f) { return (const void*)(W + d.off(l, f)); };
+        auto G = [&](int f) { return g + d.off(l, f); };
+        // three scratch buffers distinct from the one holding dcur
+        int free_idx[3], nf = 0;
+        for (int i = 0; i < 4 && nf < 3; ++i) if (i != cur_idx) free_idx[nf++] = i;
+        void* t1 = buf[free_idx[0]];
+        void* t2 = buf[free_idx[1]];
+        const int out_idx = free_idx[2];
+        void* dnext = (l == 0 && dX) ? dX : buf[out_idx];
+        const float* st1 = (const float*)(S + a.st1);
+        const float* st2 = (const float*)(S + a.st2);
+
+        if (d.causal) {
+            // y = y1 + MLP(LN2(y1))
+            TRY((colreduce<T, false>(st, dcur, nullptr, nullptr, G(B_2), d.D)));
+            TRY(linear_dw(st, S + a.h, dcur, G(W_2), d.N, d.D, d.F));
+            TRY(linear_dx(st, dcur, P(W_2), S + a.u, nullptr, dffn, d.N, d.D, d.F));
+            TRY((colreduce<T, false>(st, dffn, nullptr, nullptr, G(B_1), d.F)));
+            TRY(linear_dw(st, S + a.c, dffn, G(W_1), d.N, d.F, d.D));
+            TRY(linear_dx(st, dffn, P(W_1), nullptr, nullptr, t1, d.N, d.F, d.D));
+            TRY((colreduce<T, true>(st, t1, S + a.y1, st2, G(LN2_G), d.D)));
+            TRY(ln_bwd<T>(st, t1, S + a.y1, st2, P(LN2_G), dcur, t2));               // t2 = dy1
+            // y1 = x + Attn(LN1(x))
+            TRY((colreduce<T, false>(st, t2, nullptr, nullptr, G(B_O), d.D)));
+            TRY(linear_dw(st, S + a.o, t2, G(W_O), d.N, d.D, d.D));
+            TRY(linear_dx(st, t2, P(W_O), nullptr, nullptr, t1, d.N, d.D, d.D));       // t1 = dO
+            TRY(attention_bwd<T>(st, t1, S + a.qkv, S + a.P, dP, dqkv, valid));
+            TRY((colreduce<T, false>(st, dqkv, nullptr, nullptr, G(B_QKV), 3 * d.D)));
+            TRY(linear_dw(st, S + a.a, dqkv, G(W_QKV), d.N, 3 * d.D, d.D));
+            TRY(linear_dx(st, dqkv, P(W_QKV), nullptr, nullptr, t1, d.N, 3 * d.D, d.D));   // t1 = da
+            TRY((colreduce<T, true>(st, t1, S + a.xin, st1, G(LN1_G), d.D)));
+            TRY(ln_bwd<T>(st, t1, S + a.xin, st1, P(LN1_G), t2, dnext));
+        } else {
+            // y = LN2(r2), r2 = y1 + MLP(y1); y1 = LN1(r1), r1 = x + Attn(x)
+            TRY((colreduce<T, true>(st, dcur, S + a.c, st2, G(LN2_G), d.D)));
+            TRY(ln_bwd<T>(st, dcur, S + a.c, st2, P(LN2_G), nullptr, t2));            // t2 = dr2
+            TRY((colreduce<T, false>(st, t2, nullptr, nullptr, G(B_2), d.D)));
+            TRY(linear_dw(st, S + a.h, t2, G(W_2), d.N, d.D, d.F));
+            TRY(linear_dx(st, t2, P(W_2), S + a.u, nullptr, dffn, d.N, d.D, d.F));
+            TRY((colreduce<T, false>(st, dffn, nullptr, nullptr, G(B_1), d.F)));
+            TRY(linear_dw(st, S + a.y1, dffn, G(W_1), d.N, d.F, d.D));
+            TRY(linear_dx(st, dffn, P(W_1), nullptr, t2, t1, d.N, d.F, d.D));         // t1 = dy1
+            TRY((colreduce<T, true>(st, t1, S + a.a, st1, G(LN1_G), d.D)));
+            TRY(ln_bwd<T>(st, t1, S + a.a, st1, P(LN1_G), nullptr, t2));             // t2 = dr1
+            TRY((colreduce<T, false>(st, t2, nullptr, nullptr, G(B_O), d.D)));
+            TRY(linear_dw(st, S + a.o, t2, G(W_O), d.N, d.D, d.D));
+            TRY(linear_dx(st, t2, P(W_O), nullptr, nullptr, t1, d.N, d.D, d.D));       // t1 = dO
+            TRY(attention_bwd<T>(st, t1, S + a.qkv, S + a.P, dP, dqkv, valid));
+            TRY((colreduce<T, false>(st, dqkv, nullptr, nullptr, G(B_QKV), 3 * d.D)));
+            TRY(linear_dw(st, S + a.xin, dqkv, G(W_QKV), d.N, 3 * d.D, d.D));
+            TRY(linear_dx(st, dqkv, P(W_QKV), nullptr, t2, dnext, d.N, 3 * d.D, d.D));
+        }
+        dcur = dnext;
+        cur_idx = (l == 0 && dX) ? -1 : out_idx;
+    }
+    return AMDP_OK;
+}
+
+template <class T>
+int publish(amdp_stage* st, int vslot) {
+    const long n4 = st->d.n_alloc() / 4;
+    hipLaunchKernelGGL(publish_kernel<T>, dim3(stream_grid(n4)), dim3(STREAM_BLOCK), 0, st->stream,
+                       st->at<float>(st->w.theta), (T*)st->version_ptr(vslot), n4);
+    return after_launch();
+}
+
+}  // namespace
+
+// ================================================================== C ABI ====
+
+extern "C" size_t amdp_stage_n_params(const amdp_stage_config_t* cfg) {
+    Dims d;
+    return make_dims(cfg, &d) ? (size_t)d.n_params() : 0;
+}
+
+extern "C" size_t amdp_stage_workspace_bytes(const amdp_stage_config_t* cfg) {
+    Dims d;
+    if (!make_dims(cfg, &d)) return 0;
+    Carve w;
+    carve(d, *cfg, &w);
+    return w.total;
+}
+
+extern "C" int amdp_stage_param_layout(const amdp_stage_config_t* cfg, amdp_param_desc_t* descs, int32_t cap,
+                                       int32_t* n) {
+    Dims d;
+    if (!make_dims(cfg, &d) || !n) return AMDP_E_INVAL;
+    const int total = d.L * N_FIELDS + (d.lm ? 3 : 0);
+    *n = total;
+    if (cap < total || !descs) return AMDP_E_CAPACITY;
+    int k = 0;
+    auto put = [&](const char* name, long off, long rows, long cols) {
+        memset(&descs[k], 0, sizeof(descs[k]));
+        snprintf(descs[k].name, sizeof(descs[k].name), "%s", name);
+        descs[k].offset = (uint64_t)off; descs[k].rows = (uint32_t)rows; descs[k].cols = (uint32_t)cols;
+        ++k;
+    };
+    for (int l = 0; l < d.L; ++l)
+        for (int f = 0; f < N_FIELDS; ++f) {
+            char name[24];
+            snprintf(name, sizeof(name), "l%d.%s", l, FIELD_NAMES[f]);
+            long rows = 1, cols = d.field_size(f);
+            if (f == W_QKV) { rows = d.D; cols = 3L * d.D; }
+            if (f == W_O) { rows = d.D; cols = d.D; }
+            if (f == W_1) { rows = d.D; cols = d.F; }
+            if (f == W_2) { rows = d.F; cols = d.D; }
+            put(name, d.off(l, f), rows, cols);
+        }
+    if (d.lm) {
+        put("lnf_gamma", d.off_lnf(), 1, d.D);
+        put("lnf_beta", d.off_lnf() + d.D, 1, d.D);
+        put("embed", d.off_embed(), d.V, d.D);
+    }
+    return AMDP_OK;
+}
+
+extern "C" int amdp_stage_create(const amdp_stage_config_t* cfg, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream, amdp_stage_t** out) {
+    Dims d;
+    if (!out || !workspace || !make_dims(cfg, &d)) return AMDP_E_INVAL;
+    if ((uintptr_t)workspace % ALIGN) return AMDP_E_INVAL;
+    amdp_stage* st = new (std::nothrow) amdp_stage();
+    if (!st) return AMDP_E_INVAL;
+    st->cfg = *cfg;
+    st->d = d;
+    carve(d, *cfg, &st->w);
+    if (workspace_bytes < st->w.total) { delete st; return AMDP_E_INVAL; }
+    st->base = (char*)workspace;
+    st->stream = (hipStream_t)hip_stream;
+    st->n_vslots = cfg->stash_slots + 1;
+    if (const char* e = getenv("AMDP_GEMM_TR")) st->use_tr = atoi(e) != 0;
+    if (const char* e = getenv("AMDP_GEMM_TILE")) st->force_tile = atoi(e);
+    // parameter buffers, version slots and the padding behind them start at zero
+    if (hipMemsetAsync(st->base, 0, st->w.act, st->stream) != hipSuccess) { delete st; return AMDP_E_HIP; }
+    *out = st;
+    return AMDP_OK;
+}
+
+extern "C" int amdp_stage_destroy(amdp_stage_t* st) {
+    if (!st) return AMDP_E_INVAL;
+    delete st;
+    return AMDP_OK;
+}
+
+extern "C" int amdp_stage_set_state(amdp_stage_t* st, const float* theta, const float* m, const float* v,
+                                    uint64_t step, uint32_t version) {
+    if (!st || !theta) return AMDP_E_INVAL;
+    const size_t nb = (size_t)st->d.n_params() * 4, na = (size_t)st->d.n_alloc() * 4;
+    HIP_TRY(hipMemsetAsync(st->base + st->w.theta, 0, na, st->stream));
+    HIP_TRY(hipMemsetAsync(st->base + st->w.m, 0, na, st->stream));
+    HIP_TRY(hipMemsetAsync(st->base + st->w.v, 0, na, st->stream));
+    HIP_TRY(hipMemsetAsync(st->base + st->w.G, 0, na, st->stream));
+    HIP_TRY(hipMemsetAsync(st->base + st->w.g, 0, na, st->stream));
+    HIP_TRY(hipMemcpyAsync(st->base + st->w.theta, theta, nb, hipMemcpyDeviceToDevice, st->stream));
+    if (m) HIP_TRY(hipMemcpyAsync(st->base + st->w.m, m, nb, hipMemcpyDeviceToDevice, st->stream));
+    if (v) HIP_TRY(hipMemcpyAsync(st->base + st->w.v, v, nb, hipMemcpyDeviceToDevice, st->stream));
+    for (int i = 0; i < MAX_VSLOTS; ++i) st->vs[i] = VSlot();
+    for (int i = 0; i < MAX_ASLOTS; ++i) st->as[i] = ASlot();
+    st->staged_slot = -1;
+    st->step = step;
+    st->cur_version = version;
+    st->cur_slot = 0;
+    st->vs[0].valid = true;
+    st->vs[0].version = version;
+    return st->d.bf ? publish<bf16>(st, 0) : publish<float>(st, 0);
+}
+
+extern "C" int amdp_stage_get_state(amdp_stage_t* st, float* theta, float* m, float* v, float* G,
+                                    uint64_t* step, uint32_t* version) {
+    if (!st) return AMDP_E_INVAL;
+    const size_t nb = (size_t)st->d.n_params() * 4;
+    if (theta) HIP_TRY(hipMemcpyAsync(theta, st->base + st->w.theta, nb, hipMemcpyDeviceToDevice, st->stream));
+    if (m) HIP_TRY(hipMemcpyAsync(m, st->base + st->w.m, nb, hipMemcpyDeviceToDevice, st->stream));
+    if (v) HIP_TRY(hipMemcpyAsync(v, st->base + st->w.v, nb, hipMemcpyDeviceToDevice, st->stream));
+    if (G) HIP_TRY(hipMemcpyAsync(G, st->base + st->w.G, nb, hipMemcpyDeviceToDevice, st->stream));
+    if (step) *step = st->step;
+    if (version) *version = st->cur_version;
+    return AMDP_OK;
+}
+
+extern "C" int amdp_stage_get_staged_grad(amdp_stage_t* st, float* g) {
+    if (!st || !g) return AMDP_E_INVAL;
+    if (st->staged_slot < 0) return AMDP_E_MB_STATE;
+    HIP_TRY(hipMemcpyAsync(g, st->base + st->w.g, (size_t)st->d.n_params() * 4, hipMemcpyDeviceToDevice,
+                           st->stream));
+    return AMDP_OK;
+}
+
+extern "C" int amdp_stage_resident_versions(amdp_stage_t* st, uint32_t* versions, int32_t cap, int32_t* n) {
+    if (!st || !n) return AMDP_E_INVAL;
+    int k = 0;
+    for (int i = 0; i < st->n_vslots; ++i)
+        if (st->vs[i].valid) {
+            if (versions && k < cap) versions[k] = st->vs[i].version;
+            ++k;
+        }
+    *n = k;
+    return (versions && k > cap) ? AMDP_E_CAPACITY : AMDP_OK;
+}
+
+extern "C" int amdp_stage_forward(amdp_stage_t* st, int32_t mb, uint32_t version, const void* X,
+                                  const int32_t* aux, void* out) {
+    if (!st || !X || !out || st->cur_slot < 0) return AMDP_E_INVAL;
+    const Dims& d = st->d;
+    if ((d.lm || !d.causal) && !aux) return AMDP_E_INVAL;
+    if (st->find_mb(mb) >= 0) return AMDP_E_MB_STATE;
+    const int vslot = st->find_version(version);
+    if (vslot < 0) return AMDP_E_VERSION;
+    int aslot = -1;
+    for (int i = 0; i < st->cfg.act_slots; ++i) if (!st->as[i].used) { aslot = i; break; }
+    if (aslot < 0) return AMDP_E_NO_SLOT;
+    int rc = d.bf ? forward_impl<bf16>(st, aslot, vslot, X, aux, out)
+                  : forward_impl<float>(st, aslot, vslot, X, aux, out);
+    if (rc != AMDP_OK) return rc;
+    ASlot& a = st->as[aslot];
+    a.used = true; a.mb = mb; a.vslot = vslot; a.backwarded = false;
+    st->vs[vslot].pins++;
+    return AMDP_OK;
+}
+
+extern "C" int amdp_stage_backward(amdp_stage_t* st, int32_t mb, uint32_t version, const void* dY, void* dX) {
+    if (!st || st->cur_slot < 0) return AMDP_E_INVAL;
+    const Dims& d = st->d;
+    if (!d.lm && !dY) return AMDP_E_INVAL;
+    const int aslot = st->find_mb(mb);
+    if (aslot < 0 || st->as[aslot].backwarded) return AMDP_E_MB_STATE;
+    if (st->staged_slot >= 0) return AMDP_E_MB_STATE;
+    const int vslot = st->find_version(version);
+    if (vslot < 0) return AMDP_E_VERSION;
+    // Masked keys carry probability exactly 0, so the padding mask is not needed
+    // again: dS = P * (...) vanishes there by itself.
+    int rc = d.bf ? backward_impl<bf16>(st, aslot, vslot, nullptr, dY, dX)
+                  : backward_impl<float>(st, aslot, vslot, nullptr, dY, dX);
+    if (rc != AMDP_OK) return rc;
+    ASlot& a = st->as[aslot];
+    a.backwarded = true;
+    st->staged_slot = aslot;
+    st->vs[a.vslot].pins--;
+    st->drop_unpinned();
+    return AMDP_OK;
+}
+
+extern "C" int amdp_grad_accumulate(amdp_stage_t* st, int32_t mb) {
+    if (!st) return AMDP_E_INVAL;
+    const int aslot = st->find_mb(mb);
+    if (aslot < 0 || !st->as[aslot].backwarded || st->staged_slot != aslot) return AMDP_E_MB_STATE;
+    const long n4 = st->d.n_alloc() / 4;
+    hipLaunchKernelGGL(accumulate_kernel, dim3(stream_grid(n4)), dim3(STREAM_BLOCK), 0, st->stream,
+                       st->at<float>(st->w.G), st->at<float>(st->w.g), n4);
+    TRY(after_launch());
+    st->as[aslot] = ASlot();
+    st->staged_slot = -1;
+    return AMDP_OK;
+}
+
+extern "C" int amdp_apply_update(amdp_stage_t* st, const amdp_adam_t* hp, uint32_t* new_version) {
+    if (!st || !hp || hp->struct_size != sizeof(amdp_adam_t) || st->cur_slot < 0) return AMDP_E_INVAL;
+    if (!(hp->beta1 >= 0.f && hp->beta1 < 1.f && hp->beta2 >= 0.f && hp->beta2 < 1.f)) return AMDP_E_INVAL;
+    if (st->staged_slot >= 0) return AMDP_E_MB_STATE;   // a gradient is waiting to be accumulated
+    const int slot = st->free_vslot();
+    if (slot < 0) return AMDP_E_STASH_FULL;
+    AdamScalars sc;
+    sc.lr = hp->lr; sc.beta1 = hp->beta1; sc.beta2 = hp->beta2; sc.eps = hp->eps;
+    sc.weight_decay = hp->weight_decay; sc.grad_scale = hp->grad_scale;
+    const uint64_t t = st->step + 1;
+    if (hp->bias_correction) {
+        sc.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)hp->beta1, (double)t)));
+        sc.inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)hp->beta2, (double)t)));
+    } else {
+        sc.inv_bc1 = sc.inv_bc2 = 1.0f;
+    }
+    const long n4 = st->d.n_alloc() / 4;
+    float* th = st->at<float>(st->w.theta);
+    float* m = st->at<float>(st->w.m);
+    float* v = st->at<float>(st->w.v);
+    float* G = st->at<float>(st->w.G);
+    if (st->d.bf)
+        hipLaunchKernelGGL(adam_kernel<bf16>, dim3(stream_grid(n4)), dim3(STREAM_BLOCK), 0, st->stream, th, m,
+                           v, G, (bf16*)st->version_ptr(slot), n4, sc);
+    else
+        hipLaunchKernelGGL(adam_kernel<float>, dim3(stream_grid(n4)), dim3(STREAM_BLOCK), 0, st->stream, th,
+                           m, v, G, (float*)st->version_ptr(slot), n4, sc);
+    TRY(after_launch());
+    st->step = t;
+    st->cur_version += 1;
+    st->vs[slot].valid = true;
+    st->vs[slot].version = st->cur_version;
+    st->vs[slot].pins = 0;
+    st->cur_slot = slot;
+    st->drop_unpinned();
+    if (new_version) *new_version = st->cur_version;
+    return AMDP_OK;
+}
