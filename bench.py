@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the AMDP stage hot path on one MI355X.
+
+A step is one accumulation window of the stage's AMDP schedule in steady
+state: T minibatches' forward, backward and gradient accumulation in schedule
+order (forwards of later minibatches interleaved, each with its assigned
+weight version) plus the window's fused Adam update. Inputs are synthetic,
+seeded, and already resident in HBM when the timed region starts.
+
+Prints ONE JSON line: stage tokens/s, plus `roofline` (dominant kernel against
+the MFMA peak, timed with HIP events recorded on the launch stream inside the
+library) and `cpu_baseline` (the CPU oracle timed on the host cores on a
+bounded sample of the same workload).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3     # fp32 vector
+PEAK_HBM_GBS = 8000.0
+
+
+def algorithmic_flops_per_minibatch(w):
+    """Linear layers 2*N*(in*out) forward per matrix, attention 4*N*s_eff*D
+    forward (s_eff = (s+1)/2 causal, s otherwise), LM head 2*N*D*V forward;
+    backward = 2 x forward."""
+    N, D, F, s = w.tokens, w.d_model, w.d_ffn, w.seq_len
+    lin = 2.0 * N * (3 * D * D + D * D + 2 * D * F)
+    s_eff = (s + 1) / 2.0 if w.block_kind == 0 else float(s)
+    att = 4.0 * N * s_eff * D
+    fwd = w.n_layers * (lin + att)
+    if w.has_lm_head:
+        fwd += 2.0 * N * D * w.vocab
+    return 3.0 * fwd
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=str, default="2", help="benchmark configuration 1..5 or a test shape name")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus must be 1 "
+              "(no multi-GPU path exists, see DESIGN.md 'How the path would shard')", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2605_29664_amd as amdp
+    import workloads as W
+    from tests.parity import make_cfg
+
+    w = W.get(args.config)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    T, P = w.threshold, w.pipelines
+    K, Wu = args.steps, args.warmup
+    inflight = w.act_slots
+    M = (Wu + K + 1) * T + inflight
+
+    cfg = make_cfg(w)
+    stage = amdp.Stage(cfg, device="cuda:0")
+    layout = amdp.amdp_stage_param_layout(cfg)
+    theta0 = torch.from_numpy(W.make_theta(w, layout)).to(dev)
+    stage.amdp_stage_set_state(theta0)
+    del theta0
+
+    ring = max(2, 2 * inflight)
+    dt = stage.act_dtype
+    X = [torch.from_numpy(W.make_x(w, k)).to(dev).to(dt) for k in range(ring)]
+    dY = [None if w.has_lm_head else torch.from_numpy(W.make_dy(w, k)).to(dev).to(dt) for k in range(ring)]
+    if w.has_lm_head:
+        aux = [torch.from_numpy(W.make_targets(w, k)).to(dev) for k in range(ring)]
+        outs = [torch.empty(1, dtype=torch.float32, device=dev) for _ in range(ring)]
+    else:
+        aux = [torch.from_numpy(W.make_valid_len(w, k)).to(dev) if w.block_kind == 1 else None
+               for k in range(ring)]
+        outs = [torch.empty((w.tokens, w.d_model), dtype=dt, device=dev) for _ in range(ring)]
+    dX = torch.empty((w.tokens, w.d_model), dtype=dt, device=dev)
+
+    events = amdp.amdp_schedule_generate(w.depth, P, w.stage, T, M, w.inject_limit,
+                                         amdp.U_NEXT_BUBBLE, amdp.BWD_STASHED)
+    # split into steps: a step ends with its update
+    steps, cur = [], []
+    for e in events:
+        cur.append((e.kind, e.mb, e.version))
+        if e.kind == amdp.EV_U:
+            steps.append(cur)
+            cur = []
+    assert len(steps) >= Wu + K + 1
+
+    def run_step(evs):
+        for kind, mb, ver in evs:
+            r = mb % ring
+            if kind == amdp.EV_F:
+                stage.amdp_stage_forward(mb, ver, X[r], aux[r], outs[r])
+            elif kind == amdp.EV_B:
+                stage.amdp_stage_backward(mb, ver, dY[r], dX)
+            elif kind == amdp.EV_A:
+                stage.amdp_grad_accumulate(mb)
+            else:
+                stage.amdp_apply_update(w.lr, w.beta1, w.beta2, w.eps, w.weight_decay, 1.0 / T, True)
+
+    # step 0 holds the pipeline fill (extra forwards); it is always part of the warm-up
+    n_warm = max(1, Wu)
+    for i in range(n_warm):
+        run_step(steps[i])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(n_warm, n_warm + K):
+        run_step(steps[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    tokens = K * T * w.tokens
+    value = tokens / elapsed
+    flops_step = T * algorithmic_flops_per_minibatch(w)
+    peak = PEAK_BF16_TFLOPS if w.dtype == 1 else PEAK_FP32_TFLOPS
+
+    result = {
+        "metric": "stage tokens/sec (fwd+bwd+accumulate+update in AMDP schedule order)",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": n_warm,
+        "ms_per_step": 1e3 * elapsed / K, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if w.dtype == 1 else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "block": "gpt_preln_causal" if w.block_kind == 0 else "bert_postln_bidir",
+                   "layers": w.n_layers, "d_model": w.d_model, "heads": w.n_heads, "d_ffn": w.d_ffn,
+                   "seq_len": w.seq_len, "microbatch": w.microbatch, "vocab": w.vocab if w.has_lm_head else 0,
+                   "depth": w.depth, "pipelines": P, "stage": w.stage, "minibatches_per_update": T,
+                   "tokens_per_step": T * w.tokens, "parallelism": "1 stage on 1 GPU"},
+        "end_to_end_mfu": flops_step * K / elapsed / (peak * 1e12),
+        "algorithmic_tflop_per_step": flops_step / 1e12,
+    }
+
+    # ---- per-kernel device time from HIP events on the launch stream (a second,
+    # identical pass over one step so the events do not perturb `value`) --------
+    if not args.no_profile:
+        stage.amdp_stage_profile_begin()
+        run_step(steps[n_warm + K])
+        prof = stage.amdp_stage_profile_end()
+        table = {}
+        for name, r in sorted(prof.items(), key=lambda kv: -kv[1]["ms"]):
+            row = {"launches": r["launches"], "ms": round(r["ms"], 4)}
+            if r["flops"] > 0 and r["ms"] > 0:
+                row["tflops"] = round(r["flops"] / r["ms"] / 1e9, 2)
+            if r["bytes"] > 0 and r["ms"] > 0:
+                row["gbs"] = round(r["bytes"] / r["ms"] / 1e6, 1)
+            table[name] = row
+        result["kernels"] = table
+        gemms = {n: r for n, r in prof.items() if n.startswith("gemm_") and r["ms"] > 0}
+        if gemms:
+            dom = max(gemms, key=lambda n: gemms[n]["ms"])
+            r = gemms[dom]
+            ach = r["flops"] / r["ms"] / 1e9
+            result["roofline"] = {"kernel": dom, "bound": "mfma" if w.dtype == 1 else "alu", "achieved": ach,
+                                  "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
+                                  "launches": r["launches"], "avg_launch_ms": r["ms"] / r["launches"],
+                                  "flops_per_launch": r["flops"] / r["launches"]}
+            tot_f = sum(x["flops"] for x in gemms.values())
+            tot_ms = sum(x["ms"] for x in gemms.values())
+            result["all_gemm_kernels"] = {"tflops": tot_f / tot_ms / 1e9, "frac_of_peak": tot_f / tot_ms / 1e9 / peak,
+                                          "ms_per_step": tot_ms}
+        for nm in ("grad_accumulate", "adam_update"):
+            if nm in prof and prof[nm]["ms"] > 0:
+                gbs = prof[nm]["bytes"] / prof[nm]["ms"] / 1e6
+                result.setdefault("streaming", {})[nm] = {"gbs": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS,
+                                                          "avg_launch_ms": prof[nm]["ms"] / prof[nm]["launches"]}
+
+    stage.close()
+    del stage
+    torch.cuda.empty_cache()
+
+    # ---- the CPU oracle on the host cores, bounded sample ---------------------
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w)
+
+    print(json.dumps(result))
+
+
+def cpu_baseline(w):
+    """Times the oracle as it stands: forward + backward + accumulate of ONE
+    minibatch plus one Adam step over the stage's parameters (charged 1/T per
+    minibatch), in fp64, on the host's cores."""
+    import numpy as np
+    import workloads as W
+    from oracle import optim
+    from oracle.stage import Stage as OStage
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    ost = OStage.from_workload(w)
+    theta = W.make_theta(w, ost.layout).astype(np.float64)
+    x = W.make_x(w, 0)
+    aux = W.make_targets(w, 0) if w.has_lm_head else (W.make_valid_len(w, 0) if w.block_kind == 1 else None)
+    dy = None if w.has_lm_head else W.make_dy(w, 0)
+    t0 = time.perf_counter()
+    _, saved = ost.forward(theta, x, aux)
+    _, g = ost.backward(theta, saved, dy)
+    G = np.zeros_like(theta)
+    optim.accumulate(G, g)
+    t1 = time.perf_counter()
+    optim.adam_step(theta, np.zeros_like(theta), np.zeros_like(theta), G, 1, w.lr, w.beta1, w.beta2, w.eps)
+    t2 = time.perf_counter()
+    per_mb = (t1 - t0) + (t2 - t1) / w.threshold
+    return {"value": w.tokens / per_mb, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"1 minibatch ({w.tokens} tokens) forward+backward+accumulate in fp64 numpy "
+                      f"({t1 - t0:.1f} s) + 1/{w.threshold} of one Adam step ({t2 - t1:.2f} s)",
+            "host_cpus": os.cpu_count()}
+
+
+if __name__ == "__main__":
+    main()

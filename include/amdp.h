@@ -51,6 +51,9 @@ extern "C" {
 #define AMDP_E_CAPACITY   -7  /* caller's output array is too small; *n_out holds the need */
 
 const char* amdp_strerror(int code);
+/* Text of the HIP error behind the calling thread's most recent AMDP_E_HIP
+ * ("" if none): which call failed and hipGetErrorString of its status. */
+const char* amdp_last_hip_error(void);
 
 /* ------------------------------------------------------------------------
  * Schedule generator (host only, integers only, no GPU needed)
@@ -227,10 +230,13 @@ int amdp_grad_accumulate(amdp_stage_t* stage, int32_t mb);
 
 typedef struct amdp_adam_t {
     uint32_t struct_size;
-    float lr, beta1, beta2, eps;
-    float weight_decay;     /* decoupled (AdamW); 0 in all benchmark configurations */
-    float grad_scale;       /* the update consumes grad_scale * G, e.g. 1/T */
     int32_t bias_correction; /* 1: divide moments by (1 - beta^t); 0: the form printed in Appendix B.1 */
+    /* Hyper-parameters are doubles so that derived constants (1 - beta, the
+     * bias corrections) are formed exactly on the host and rounded to fp32
+     * once; the kernel's arithmetic is fp32. */
+    double lr, beta1, beta2, eps;
+    double weight_decay;     /* decoupled (AdamW); 0 in all benchmark configurations */
+    double grad_scale;       /* the update consumes grad_scale * G, e.g. 1/T */
 } amdp_adam_t;
 
 /* One Adam step over the flat fp32 master parameters with the accumulated
@@ -239,6 +245,28 @@ typedef struct amdp_adam_t {
  * G cleared. *new_version (host, may be NULL) receives its number. Older
  * versions stay resident while an in-flight minibatch's forward has read them. */
 int amdp_apply_update(amdp_stage_t* stage, const amdp_adam_t* hp, uint32_t* new_version);
+
+/* ------------------------------------------------------------------------
+ * Measurement aid: per-kernel-class device time from HIP events recorded on
+ * the stage's stream around every launch between begin and end. `flops` and
+ * `bytes` are the ALGORITHMIC work of the launches (2MNK per GEMM, only
+ * visible query/key pairs under the causal mask; 12 bytes per parameter for
+ * the accumulation, 32 + sizeof(stage dtype) per parameter for the update).
+ * Profiling inserts events into the stream: do not time throughput while on.
+ * amdp_stage_profile_end synchronises the stream.
+ * ------------------------------------------------------------------------ */
+typedef struct amdp_profile_entry_t {
+    char     name[48];
+    uint64_t launches;
+    double   ms;      /* summed event-to-event time of those launches */
+    double   flops;
+    double   bytes;
+} amdp_profile_entry_t;
+
+int amdp_stage_profile_begin(amdp_stage_t* stage);
+/* out: host array; AMDP_E_CAPACITY (with *n set) if cap is too small -- the
+ * recorded data is discarded either way. */
+int amdp_stage_profile_end(amdp_stage_t* stage, amdp_profile_entry_t* out, int32_t cap, int32_t* n);
 
 #ifdef __cplusplus
 }

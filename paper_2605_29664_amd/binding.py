@@ -21,7 +21,10 @@ E_INVAL, E_MB_STATE, E_NO_SLOT, E_VERSION, E_STASH_FULL, E_HIP, E_CAPACITY = -1,
 class AmdpError(RuntimeError):
     def __init__(self, code, what=""):
         self.code = code
-        super().__init__(f"{what}: {amdp_strerror(code)} ({code})")
+        detail = ""
+        if code == E_HIP:
+            detail = " [" + lib().amdp_last_hip_error().decode() + "]"
+        super().__init__(f"{what}: {amdp_strerror(code)} ({code}){detail}")
 
 
 class amdp_event_t(C.Structure):
@@ -55,10 +58,15 @@ class amdp_param_desc_t(C.Structure):
                 ("cols", C.c_uint32)]
 
 
+class amdp_profile_entry_t(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("launches", C.c_uint64), ("ms", C.c_double),
+                ("flops", C.c_double), ("bytes", C.c_double)]
+
+
 class amdp_adam_t(C.Structure):
-    _fields_ = [("struct_size", C.c_uint32), ("lr", C.c_float), ("beta1", C.c_float),
-                ("beta2", C.c_float), ("eps", C.c_float), ("weight_decay", C.c_float),
-                ("grad_scale", C.c_float), ("bias_correction", C.c_int32)]
+    _fields_ = [("struct_size", C.c_uint32), ("bias_correction", C.c_int32), ("lr", C.c_double),
+                ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
+                ("weight_decay", C.c_double), ("grad_scale", C.c_double)]
 
 
 def lib_path():
@@ -91,6 +99,11 @@ def lib():
     global _lib
     if _lib is not None:
         return _lib
+    # PyTorch ships its own HIP runtime under the same soname as the system's.
+    # Import it first so that this library binds to the runtime instance that
+    # owns the process's device context and streams; loading in the other
+    # order leaves two half-initialised runtimes ("no ROCm-capable device").
+    import torch  # noqa: F401
     path = lib_path()
     if not os.path.exists(path):
         raise ImportError(f"{path} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
@@ -99,6 +112,7 @@ def lib():
     P = C.POINTER
     sigs = {
         "amdp_strerror": (C.c_char_p, [C.c_int]),
+        "amdp_last_hip_error": (C.c_char_p, []),
         "amdp_schedule_generate": (C.c_int, [P(amdp_sched_params_t), P(amdp_event_t), sz, P(sz)]),
         "amdp_schedule_stats": (C.c_int, [P(amdp_event_t), sz, i32, P(amdp_sched_stats_t)]),
         "amdp_stage_map": (C.c_int, [i32, i32, i32, P(i32)]),
@@ -115,6 +129,8 @@ def lib():
         "amdp_stage_backward": (C.c_int, [vp, i32, u32, vp, vp]),
         "amdp_grad_accumulate": (C.c_int, [vp, i32]),
         "amdp_apply_update": (C.c_int, [vp, P(amdp_adam_t), P(u32)]),
+        "amdp_stage_profile_begin": (C.c_int, [vp]),
+        "amdp_stage_profile_end": (C.c_int, [vp, P(amdp_profile_entry_t), i32, P(i32)]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(L, name)
@@ -124,11 +140,12 @@ def lib():
     return L
 
 
-EXPORTED = ["amdp_strerror", "amdp_schedule_generate", "amdp_schedule_stats", "amdp_stage_map",
+EXPORTED = ["amdp_strerror", "amdp_last_hip_error", "amdp_schedule_generate", "amdp_schedule_stats", "amdp_stage_map",
             "amdp_stage_n_params", "amdp_stage_workspace_bytes", "amdp_stage_param_layout",
             "amdp_stage_create", "amdp_stage_destroy", "amdp_stage_set_state", "amdp_stage_get_state",
             "amdp_stage_get_staged_grad", "amdp_stage_resident_versions", "amdp_stage_forward",
-            "amdp_stage_backward", "amdp_grad_accumulate", "amdp_apply_update"]
+            "amdp_stage_backward", "amdp_grad_accumulate", "amdp_apply_update",
+            "amdp_stage_profile_begin", "amdp_stage_profile_end"]
 
 
 def _check(rc, what):
@@ -192,9 +209,19 @@ def amdp_stage_param_layout(cfg):
     return [(d.name.decode(), int(d.offset), int(d.rows), int(d.cols)) for d in arr]
 
 
-def _ptr(t):
+def _ptr(t, dtype=None, numel=None, device=None):
+    """Device address of a tensor after checking that it is what the C ABI
+    expects: right element type, contiguous, on the stage's GPU, big enough."""
     if t is None:
         return None
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected a {dtype} tensor, got {t.dtype}")
+    if not t.is_contiguous():
+        raise TypeError("tensor must be contiguous")
+    if device is not None and t.device != device:
+        raise TypeError(f"tensor is on {t.device}, the stage on {device}")
+    if numel is not None and t.numel() < numel:
+        raise ValueError(f"tensor has {t.numel()} elements, {numel} needed")
     return C.c_void_p(t.data_ptr())
 
 
@@ -203,7 +230,7 @@ class Stage:
     names of the C entry points they call. Tensors must live on the stage's
     device; nothing here synchronises."""
 
-    def __init__(self, cfg, device="cuda:0", stream=None):
+    def __init__(self, cfg, device="cuda:0", stream=None, poison=False):
         import torch
         self.torch = torch
         self.cfg = cfg
@@ -216,6 +243,8 @@ class Stage:
         self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         with torch.cuda.device(self.device):
             self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+            if poison:   # test aid: every byte 0xFF reads as NaN in fp32 and bf16
+                self.workspace.fill_(255)
             base = self.workspace.data_ptr()
             self._ws_ptr = (base + 255) // 256 * 256
             h = C.c_void_p()
@@ -224,6 +253,14 @@ class Stage:
                    "amdp_stage_create")
         self.handle = h
         self.act_dtype = torch.bfloat16 if cfg.dtype == BF16 else torch.float32
+        self.tokens = cfg.seq_len * cfg.microbatch
+        self.device = self.workspace.device
+
+    def _p32(self, t):
+        return _ptr(t, self.torch.float32, self.n_params, self.device)
+
+    def _act(self, t):
+        return _ptr(t, self.act_dtype, self.tokens * self.cfg.d_model, self.device)
 
     def close(self):
         if getattr(self, "handle", None):
@@ -237,17 +274,17 @@ class Stage:
             pass
 
     def amdp_stage_set_state(self, theta, m=None, v=None, step=0, version=0):
-        _check(lib().amdp_stage_set_state(self.handle, _ptr(theta), _ptr(m), _ptr(v), step, version),
-               "amdp_stage_set_state")
+        _check(lib().amdp_stage_set_state(self.handle, self._p32(theta), self._p32(m), self._p32(v), step,
+                                          version), "amdp_stage_set_state")
 
     def amdp_stage_get_state(self, theta=None, m=None, v=None, G=None):
         step, ver = C.c_uint64(0), C.c_uint32(0)
-        _check(lib().amdp_stage_get_state(self.handle, _ptr(theta), _ptr(m), _ptr(v), _ptr(G),
-                                          C.byref(step), C.byref(ver)), "amdp_stage_get_state")
+        _check(lib().amdp_stage_get_state(self.handle, self._p32(theta), self._p32(m), self._p32(v),
+                                          self._p32(G), C.byref(step), C.byref(ver)), "amdp_stage_get_state")
         return step.value, ver.value
 
     def amdp_stage_get_staged_grad(self, g):
-        _check(lib().amdp_stage_get_staged_grad(self.handle, _ptr(g)), "amdp_stage_get_staged_grad")
+        _check(lib().amdp_stage_get_staged_grad(self.handle, self._p32(g)), "amdp_stage_get_staged_grad")
 
     def amdp_stage_resident_versions(self):
         arr = (C.c_uint32 * 32)()
@@ -257,11 +294,17 @@ class Stage:
         return sorted(arr[i] for i in range(n.value))
 
     def amdp_stage_forward(self, mb, version, X, aux, out):
-        _check(lib().amdp_stage_forward(self.handle, mb, version, _ptr(X), _ptr(aux), _ptr(out)),
-               "amdp_stage_forward")
+        torch = self.torch
+        if self.cfg.has_lm_head:
+            a = _ptr(aux, torch.int32, self.tokens, self.device)
+            o = _ptr(out, torch.float32, 1, self.device)
+        else:
+            a = _ptr(aux, torch.int32, self.cfg.microbatch, self.device)
+            o = self._act(out)
+        _check(lib().amdp_stage_forward(self.handle, mb, version, self._act(X), a, o), "amdp_stage_forward")
 
     def amdp_stage_backward(self, mb, version, dY, dX):
-        _check(lib().amdp_stage_backward(self.handle, mb, version, _ptr(dY), _ptr(dX)),
+        _check(lib().amdp_stage_backward(self.handle, mb, version, self._act(dY), self._act(dX)),
                "amdp_stage_backward")
 
     def amdp_grad_accumulate(self, mb):
@@ -269,8 +312,19 @@ class Stage:
 
     def amdp_apply_update(self, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, grad_scale=1.0,
                           bias_correction=True):
-        hp = amdp_adam_t(C.sizeof(amdp_adam_t), lr, beta1, beta2, eps, weight_decay, grad_scale,
-                         int(bool(bias_correction)))
+        hp = amdp_adam_t(C.sizeof(amdp_adam_t), int(bool(bias_correction)), lr, beta1, beta2, eps,
+                         weight_decay, grad_scale)
         nv = C.c_uint32(0)
         _check(lib().amdp_apply_update(self.handle, C.byref(hp), C.byref(nv)), "amdp_apply_update")
         return nv.value
+
+    def amdp_stage_profile_begin(self):
+        _check(lib().amdp_stage_profile_begin(self.handle), "amdp_stage_profile_begin")
+
+    def amdp_stage_profile_end(self):
+        """{name: dict(launches, ms, flops, bytes)}"""
+        arr = (amdp_profile_entry_t * 64)()
+        n = C.c_int32(0)
+        _check(lib().amdp_stage_profile_end(self.handle, arr, 64, C.byref(n)), "amdp_stage_profile_end")
+        return {arr[i].name.decode(): dict(launches=int(arr[i].launches), ms=arr[i].ms, flops=arr[i].flops,
+                                           bytes=arr[i].bytes) for i in range(n.value)}

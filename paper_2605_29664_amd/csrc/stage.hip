@@ -15,6 +15,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <string>
 #include <vector>
 
 using namespace amdp;
@@ -148,6 +149,19 @@ void carve(const Dims& d, const amdp_stage_config_t& c, Carve* w) {
     w->total = off;
 }
 
+// Optional per-launch timing with HIP events on the stage's stream.
+struct ProfRecord { int name_id; hipEvent_t start, stop; double flops, bytes; };
+struct Profiler {
+    bool on = false;
+    std::vector<std::string> names;
+    std::vector<ProfRecord> recs;
+    int id_of(const char* name) {
+        for (size_t i = 0; i < names.size(); ++i) if (names[i] == name) return (int)i;
+        names.emplace_back(name);
+        return (int)names.size() - 1;
+    }
+};
+
 struct VSlot { bool valid = false; uint32_t version = 0; int pins = 0; };
 struct ASlot { bool used = false; int32_t mb = 0; int vslot = -1; bool backwarded = false; };
 
@@ -168,6 +182,7 @@ struct amdp_stage {
     int staged_slot = -1;   // activation slot whose gradient sits in the staging buffer
     bool use_tr = true;
     int force_tile = 0;
+    Profiler prof;
 
     template <class P = void> P* at(size_t off) const { return (P*)(base + off); }
     char* version_ptr(int slot) const { return base + w.versions + (size_t)slot * w.version_bytes; }
@@ -195,10 +210,63 @@ struct amdp_stage {
 
 namespace {
 
-#define HIP_TRY(expr) do { if ((expr) != hipSuccess) return AMDP_E_HIP; } while (0)
+thread_local char g_hip_detail[160] = "";
+inline bool hip_ok(hipError_t e, const char* what) {
+    if (e == hipSuccess) return true;
+    snprintf(g_hip_detail, sizeof(g_hip_detail), "%s: %s", what, hipGetErrorString(e));
+    return false;
+}
+#define HIP_TRY(expr) do { if (!hip_ok((expr), #expr)) return AMDP_E_HIP; } while (0)
 #define TRY(expr) do { int rc_ = (expr); if (rc_ != AMDP_OK) return rc_; } while (0)
 
-inline int after_launch() { return hipGetLastError() == hipSuccess ? AMDP_OK : AMDP_E_HIP; }
+inline int after_launch() { return hip_ok(hipGetLastError(), "kernel launch") ? AMDP_OK : AMDP_E_HIP; }
+
+// bytes is a multiple of 4; 16-byte path when both pointers allow it
+int device_copy(hipStream_t stream, void* dst, const void* src, size_t bytes) {
+    if (!bytes) return AMDP_OK;
+    if ((((uintptr_t)dst | (uintptr_t)src) & 15) == 0 && bytes % 16 == 0) {
+        const long n16 = (long)(bytes / 16);
+        hipLaunchKernelGGL(copy16_kernel, dim3(stream_grid(n16)), dim3(STREAM_BLOCK), 0, stream, (u32x4*)dst,
+                           (const u32x4*)src, n16);
+    } else {
+        if ((((uintptr_t)dst | (uintptr_t)src) & 3) || bytes % 4) return AMDP_E_INVAL;
+        const long n = (long)(bytes / 4);
+        hipLaunchKernelGGL(copy4_kernel, dim3(stream_grid(n)), dim3(STREAM_BLOCK), 0, stream, (uint32_t*)dst,
+                           (const uint32_t*)src, n);
+    }
+    return after_launch();
+}
+// dst 16-byte aligned, bytes a multiple of 16 (all workspace regions are)
+int device_zero(hipStream_t stream, void* dst, size_t bytes) {
+    if (!bytes) return AMDP_OK;
+    const long n16 = (long)(bytes / 16);
+    hipLaunchKernelGGL(zero16_kernel, dim3(stream_grid(n16)), dim3(STREAM_BLOCK), 0, stream, (u32x4*)dst, n16);
+    return after_launch();
+}
+
+// Brackets the launches made during its lifetime with two events when the
+// stage's profiler is on; costs one branch otherwise.
+struct ProfScope {
+    amdp_stage* st;
+    int idx = -1;
+    ProfScope(amdp_stage* s, const char* name, double flops, double bytes) : st(s) {
+        if (!st->prof.on) return;
+        ProfRecord r{st->prof.id_of(name), nullptr, nullptr, flops, bytes};
+        if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
+        hipEventRecord(r.start, st->stream);
+        st->prof.recs.push_back(r);
+        idx = (int)st->prof.recs.size() - 1;
+    }
+    ~ProfScope() {
+        if (idx >= 0) hipEventRecord(st->prof.recs[idx].stop, st->stream);
+    }
+};
+
+inline double gemm_flops(const GemmArgs& g) {
+    double f = 2.0 * g.M * (double)g.N * g.K * g.batch;
+    if (g.causal) f *= (g.M + 1.0) / (2.0 * g.M);   // only query/key pairs with key <= query
+    return f;
+}
 
 // ---- GEMM dispatch ----------------------------------------------------------
 template <bool A_KM, bool B_KM>
@@ -216,6 +284,10 @@ int gemm_bf16_layout(amdp_stage* st, const GemmArgs& g) {
     if (st->force_tile == 128 && ok128) tile = 128;
     if (st->force_tile == 256 && ok256) tile = 256;
     if (st->force_tile < 0) tile = 0;
+    char name[48];
+    snprintf(name, sizeof(name), "gemm_%s_%s%s", tile == 256 ? "mfma256x256" : tile == 128 ? "mfma128x128"
+             : tile == 64 ? "mfma128x64" : "generic", A_KM ? "TN" : (B_KM ? "NN" : "NT"), g.batch > 1 ? "_batched" : "");
+    ProfScope ps(st, name, gemm_flops(g), 0.0);
     switch (tile) {
         case 256:
             e = tr ? launch_gemm_mfma_inst<256, 256, A_KM, B_KM, true>(g, st->stream)
@@ -232,7 +304,7 @@ int gemm_bf16_layout(amdp_stage* st, const GemmArgs& g) {
         default:
             e = launch_gemm_simple<bf16>(g, st->stream);
     }
-    return e == hipSuccess ? AMDP_OK : AMDP_E_HIP;
+    return hip_ok(e, name) ? AMDP_OK : AMDP_E_HIP;
 }
 
 enum GemmLayout { G_NN, G_NT, G_TN };
@@ -246,7 +318,10 @@ int gemm(amdp_stage* st, GemmLayout lay, GemmArgs g, long lda, long ldb) {
         case G_TN: g.a_rs = 1; g.a_cs = lda; g.b_rs = ldb; g.b_cs = 1; break;
     }
     if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return AMDP_OK;
-    if (!st->d.bf) return launch_gemm_simple<float>(g, st->stream) == hipSuccess ? AMDP_OK : AMDP_E_HIP;
+    if (!st->d.bf) {
+        ProfScope ps(st, "gemm_generic_fp32", gemm_flops(g), 0.0);
+        return hip_ok(launch_gemm_simple<float>(g, st->stream), "gemm_generic_fp32") ? AMDP_OK : AMDP_E_HIP;
+    }
     switch (lay) {
         case G_NN: return gemm_bf16_layout<false, true>(st, g);
         case G_NT: return gemm_bf16_layout<false, false>(st, g);
@@ -258,6 +333,7 @@ int gemm(amdp_stage* st, GemmLayout lay, GemmArgs g, long lda, long ldb) {
 template <class T>
 int ln_fwd(amdp_stage* st, const void* x, const void* gamma, const void* beta, void* y, float* stats) {
     const Dims& d = st->d;
+    ProfScope ps(st, "layernorm_fwd", 0.0, (double)d.N * d.D * sizeof(T) * 2);
     hipLaunchKernelGGL(ln_fwd_kernel<T>, dim3((d.N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0,
                        st->stream, (const T*)x, (const T*)gamma, (const T*)beta, (T*)y, stats, d.N, d.D,
                        st->cfg.ln_eps);
@@ -267,6 +343,7 @@ template <class T>
 int ln_bwd(amdp_stage* st, const void* dy, const void* x, const float* stats, const void* gamma,
            const void* res, void* dx) {
     const Dims& d = st->d;
+    ProfScope ps(st, "layernorm_bwd", 0.0, (double)d.N * d.D * sizeof(T) * (res ? 4 : 3));
     hipLaunchKernelGGL(ln_bwd_kernel<T>, dim3((d.N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0,
                        st->stream, (const T*)dy, (const T*)x, stats, (const T*)gamma, (const T*)res, (T*)dx,
                        d.N, d.D);
@@ -279,6 +356,7 @@ int colreduce(amdp_stage* st, const void* dy, const void* x, const float* stats,
     const int rpc = std::max(16, (d.N + st->w.partial_chunks - 1) / st->w.partial_chunks);
     const int chunks = (d.N + rpc - 1) / rpc;
     float* partial = st->at<float>(st->w.partial);
+    ProfScope ps(st, LN ? "colreduce_ln" : "colreduce_bias", 0.0, (double)d.N * C * sizeof(T) * (LN ? 2 : 1));
     hipLaunchKernelGGL((colreduce_partial_kernel<T, LN>), dim3((C + 255) / 256, chunks), dim3(256), 0,
                        st->stream, (const T*)dy, (const T*)x, stats, partial, d.N, C, rpc);
     TRY(after_launch());
@@ -310,9 +388,12 @@ int attention_fwd(amdp_stage* st, const void* qkv_, void* P_, void* o_, const in
         TRY(gemm(st, G_NT, g, ld3, ld3));
     }
     const long rows = (long)d.b * d.H * d.s;
+    {
+    ProfScope ps(st, "softmax_fwd", 0.0, (double)rows * d.s * sizeof(T) * (d.causal ? 1.5 : 2.0));
     hipLaunchKernelGGL(softmax_fwd_kernel<T>, dim3((unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK)),
                        dim3(256), 0, st->stream, (T*)P_, rows, d.s, 1.0f / sqrtf((float)d.dh),
                        d.causal ? 1 : 0, valid, d.H);
+    }
     TRY(after_launch());
     {   // O = P V
         GemmArgs g = attn_batch(d);
@@ -355,9 +436,12 @@ int attention_bwd(amdp_stage* st, const void* dO_, const void* qkv_, const void*
         TRY(gemm(st, G_NT, g, d.D, ld3));
     }
     const long rows = (long)d.b * d.H * d.s;
+    {
+    ProfScope ps(st, "softmax_bwd", 0.0, (double)rows * d.s * sizeof(T) * (d.causal ? 2.0 : 3.0));
     hipLaunchKernelGGL(softmax_bwd_kernel<T>, dim3((unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK)),
                        dim3(256), 0, st->stream, (const T*)P_, (T*)dP_, rows, d.s, 1.0f / sqrtf((float)d.dh),
                        d.causal ? 1 : 0, valid, d.H);
+    }
     TRY(after_launch());
     {   // dQ = dS K
         GemmArgs g = attn_batch(d);
@@ -410,7 +494,10 @@ int forward_impl(amdp_stage* st, int aslot, int vslot, const void* X, const int3
     const size_t ND = (size_t)d.N * d.D * sizeof(T);
     // aux is the padding mask for bidirectional blocks, the targets on an LM-head stage
     const int32_t* valid = (!d.causal && !d.lm) ? aux : nullptr;
-    HIP_TRY(hipMemcpyAsync(S + st->w.slot.layers[0].xin, X, ND, hipMemcpyDeviceToDevice, st->stream));
+    {
+        ProfScope ps(st, "copy_input", 0.0, 2.0 * (double)ND);
+        TRY(device_copy(st->stream, S + st->w.slot.layers[0].xin, X, ND));
+    }
     for (int l = 0; l < d.L; ++l) {
         const LayerAct& a = st->w.slot.layers[l];
         void* xin = S + a.xin;
@@ -444,6 +531,7 @@ int forward_impl(amdp_stage* st, int aslot, int vslot, const void* X, const int3
         g.M = d.N; g.N = (int)d.Vld; g.K = d.D; g.ldc = d.Vld;
         TRY(gemm(st, G_NT, g, d.D, d.D));
         float* row_loss = st->at<float>(st->w.row_loss);
+        ProfScope ps(st, "cross_entropy", 0.0, (double)d.N * d.V * sizeof(T) * 2);
         hipLaunchKernelGGL(ce_fwd_kernel<T>, dim3((d.N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0,
                            st->stream, (T*)(S + sl.dlogits), aux, row_loss, d.N, d.V, d.Vld);
         TRY(after_launch());
@@ -622,7 +710,10 @@ extern "C" int amdp_stage_create(const amdp_stage_config_t* cfg, void* workspace
     if (const char* e = getenv("AMDP_GEMM_TR")) st->use_tr = atoi(e) != 0;
     if (const char* e = getenv("AMDP_GEMM_TILE")) st->force_tile = atoi(e);
     // parameter buffers, version slots and the padding behind them start at zero
-    if (hipMemsetAsync(st->base, 0, st->w.act, st->stream) != hipSuccess) { delete st; return AMDP_E_HIP; }
+    if (device_zero(st->stream, st->base, st->w.act) != AMDP_OK) {
+        delete st;
+        return AMDP_E_HIP;
+    }
     *out = st;
     return AMDP_OK;
 }
@@ -637,14 +728,15 @@ extern "C" int amdp_stage_set_state(amdp_stage_t* st, const float* theta, const 
                                     uint64_t step, uint32_t version) {
     if (!st || !theta) return AMDP_E_INVAL;
     const size_t nb = (size_t)st->d.n_params() * 4, na = (size_t)st->d.n_alloc() * 4;
-    HIP_TRY(hipMemsetAsync(st->base + st->w.theta, 0, na, st->stream));
-    HIP_TRY(hipMemsetAsync(st->base + st->w.m, 0, na, st->stream));
-    HIP_TRY(hipMemsetAsync(st->base + st->w.v, 0, na, st->stream));
-    HIP_TRY(hipMemsetAsync(st->base + st->w.G, 0, na, st->stream));
-    HIP_TRY(hipMemsetAsync(st->base + st->w.g, 0, na, st->stream));
-    HIP_TRY(hipMemcpyAsync(st->base + st->w.theta, theta, nb, hipMemcpyDeviceToDevice, st->stream));
-    if (m) HIP_TRY(hipMemcpyAsync(st->base + st->w.m, m, nb, hipMemcpyDeviceToDevice, st->stream));
-    if (v) HIP_TRY(hipMemcpyAsync(st->base + st->w.v, v, nb, hipMemcpyDeviceToDevice, st->stream));
+    if ((uintptr_t)theta % 4 || (uintptr_t)m % 4 || (uintptr_t)v % 4) return AMDP_E_INVAL;
+    TRY(device_zero(st->stream, st->base + st->w.theta, na));
+    TRY(device_zero(st->stream, st->base + st->w.m, na));
+    TRY(device_zero(st->stream, st->base + st->w.v, na));
+    TRY(device_zero(st->stream, st->base + st->w.G, na));
+    TRY(device_zero(st->stream, st->base + st->w.g, na));
+    TRY(device_copy(st->stream, st->base + st->w.theta, theta, nb));
+    if (m) TRY(device_copy(st->stream, st->base + st->w.m, m, nb));
+    if (v) TRY(device_copy(st->stream, st->base + st->w.v, v, nb));
     for (int i = 0; i < MAX_VSLOTS; ++i) st->vs[i] = VSlot();
     for (int i = 0; i < MAX_ASLOTS; ++i) st->as[i] = ASlot();
     st->staged_slot = -1;
@@ -660,10 +752,11 @@ extern "C" int amdp_stage_get_state(amdp_stage_t* st, float* theta, float* m, fl
                                     uint64_t* step, uint32_t* version) {
     if (!st) return AMDP_E_INVAL;
     const size_t nb = (size_t)st->d.n_params() * 4;
-    if (theta) HIP_TRY(hipMemcpyAsync(theta, st->base + st->w.theta, nb, hipMemcpyDeviceToDevice, st->stream));
-    if (m) HIP_TRY(hipMemcpyAsync(m, st->base + st->w.m, nb, hipMemcpyDeviceToDevice, st->stream));
-    if (v) HIP_TRY(hipMemcpyAsync(v, st->base + st->w.v, nb, hipMemcpyDeviceToDevice, st->stream));
-    if (G) HIP_TRY(hipMemcpyAsync(G, st->base + st->w.G, nb, hipMemcpyDeviceToDevice, st->stream));
+    if (((uintptr_t)theta | (uintptr_t)m | (uintptr_t)v | (uintptr_t)G) % 4) return AMDP_E_INVAL;
+    if (theta) TRY(device_copy(st->stream, theta, st->base + st->w.theta, nb));
+    if (m) TRY(device_copy(st->stream, m, st->base + st->w.m, nb));
+    if (v) TRY(device_copy(st->stream, v, st->base + st->w.v, nb));
+    if (G) TRY(device_copy(st->stream, G, st->base + st->w.G, nb));
     if (step) *step = st->step;
     if (version) *version = st->cur_version;
     return AMDP_OK;
@@ -672,9 +765,8 @@ extern "C" int amdp_stage_get_state(amdp_stage_t* st, float* theta, float* m, fl
 extern "C" int amdp_stage_get_staged_grad(amdp_stage_t* st, float* g) {
     if (!st || !g) return AMDP_E_INVAL;
     if (st->staged_slot < 0) return AMDP_E_MB_STATE;
-    HIP_TRY(hipMemcpyAsync(g, st->base + st->w.g, (size_t)st->d.n_params() * 4, hipMemcpyDeviceToDevice,
-                           st->stream));
-    return AMDP_OK;
+    if ((uintptr_t)g % 4) return AMDP_E_INVAL;
+    return device_copy(st->stream, g, st->base + st->w.g, (size_t)st->d.n_params() * 4);
 }
 
 extern "C" int amdp_stage_resident_versions(amdp_stage_t* st, uint32_t* versions, int32_t cap, int32_t* n) {
@@ -736,6 +828,7 @@ extern "C" int amdp_grad_accumulate(amdp_stage_t* st, int32_t mb) {
     const int aslot = st->find_mb(mb);
     if (aslot < 0 || !st->as[aslot].backwarded || st->staged_slot != aslot) return AMDP_E_MB_STATE;
     const long n4 = st->d.n_alloc() / 4;
+    ProfScope ps(st, "grad_accumulate", 0.0, 12.0 * (double)st->d.n_params());
     hipLaunchKernelGGL(accumulate_kernel, dim3(stream_grid(n4)), dim3(STREAM_BLOCK), 0, st->stream,
                        st->at<float>(st->w.G), st->at<float>(st->w.g), n4);
     TRY(after_launch());
@@ -746,17 +839,18 @@ extern "C" int amdp_grad_accumulate(amdp_stage_t* st, int32_t mb) {
 
 extern "C" int amdp_apply_update(amdp_stage_t* st, const amdp_adam_t* hp, uint32_t* new_version) {
     if (!st || !hp || hp->struct_size != sizeof(amdp_adam_t) || st->cur_slot < 0) return AMDP_E_INVAL;
-    if (!(hp->beta1 >= 0.f && hp->beta1 < 1.f && hp->beta2 >= 0.f && hp->beta2 < 1.f)) return AMDP_E_INVAL;
+    if (!(hp->beta1 >= 0.0 && hp->beta1 < 1.0 && hp->beta2 >= 0.0 && hp->beta2 < 1.0)) return AMDP_E_INVAL;
     if (st->staged_slot >= 0) return AMDP_E_MB_STATE;   // a gradient is waiting to be accumulated
     const int slot = st->free_vslot();
     if (slot < 0) return AMDP_E_STASH_FULL;
     AdamScalars sc;
-    sc.lr = hp->lr; sc.beta1 = hp->beta1; sc.beta2 = hp->beta2; sc.eps = hp->eps;
-    sc.weight_decay = hp->weight_decay; sc.grad_scale = hp->grad_scale;
+    sc.lr = (float)hp->lr; sc.beta1 = (float)hp->beta1; sc.beta2 = (float)hp->beta2; sc.eps = (float)hp->eps;
+    sc.weight_decay = (float)hp->weight_decay; sc.grad_scale = (float)hp->grad_scale;
+    sc.omb1 = (float)(1.0 - hp->beta1); sc.omb2 = (float)(1.0 - hp->beta2);
     const uint64_t t = st->step + 1;
     if (hp->bias_correction) {
-        sc.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)hp->beta1, (double)t)));
-        sc.inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)hp->beta2, (double)t)));
+        sc.inv_bc1 = (float)(1.0 / (1.0 - std::pow(hp->beta1, (double)t)));
+        sc.inv_bc2 = (float)(1.0 / (1.0 - std::pow(hp->beta2, (double)t)));
     } else {
         sc.inv_bc1 = sc.inv_bc2 = 1.0f;
     }
@@ -765,6 +859,8 @@ extern "C" int amdp_apply_update(amdp_stage_t* st, const amdp_adam_t* hp, uint32
     float* m = st->at<float>(st->w.m);
     float* v = st->at<float>(st->w.v);
     float* G = st->at<float>(st->w.G);
+    // read theta, m, v, G; write theta, m, v, the new version, and G = 0
+    ProfScope ps(st, "adam_update", 0.0, (32.0 + (double)st->d.esz) * (double)st->d.n_params());
     if (st->d.bf)
         hipLaunchKernelGGL(adam_kernel<bf16>, dim3(stream_grid(n4)), dim3(STREAM_BLOCK), 0, st->stream, th, m,
                            v, G, (bf16*)st->version_ptr(slot), n4, sc);
@@ -782,3 +878,40 @@ extern "C" int amdp_apply_update(amdp_stage_t* st, const amdp_adam_t* hp, uint32
     if (new_version) *new_version = st->cur_version;
     return AMDP_OK;
 }
+
+extern "C" int amdp_stage_profile_begin(amdp_stage_t* st) {
+    if (!st || st->prof.on) return AMDP_E_INVAL;
+    st->prof.names.clear();
+    st->prof.recs.clear();
+    st->prof.on = true;
+    return AMDP_OK;
+}
+
+extern "C" int amdp_stage_profile_end(amdp_stage_t* st, amdp_profile_entry_t* out, int32_t cap, int32_t* n) {
+    if (!st || !n || !st->prof.on) return AMDP_E_INVAL;
+    st->prof.on = false;
+    int rc = AMDP_OK;
+    if (hipStreamSynchronize(st->stream) != hipSuccess) rc = AMDP_E_HIP;
+    std::vector<amdp_profile_entry_t> agg(st->prof.names.size());
+    for (size_t i = 0; i < agg.size(); ++i) {
+        memset(&agg[i], 0, sizeof(agg[i]));
+        snprintf(agg[i].name, sizeof(agg[i].name), "%s", st->prof.names[i].c_str());
+    }
+    for (ProfRecord& r : st->prof.recs) {
+        float ms = 0.f;
+        if (rc == AMDP_OK && hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
+            amdp_profile_entry_t& e = agg[r.name_id];
+            e.launches += 1; e.ms += ms; e.flops += r.flops; e.bytes += r.bytes;
+        }
+        hipEventDestroy(r.start);
+        hipEventDestroy(r.stop);
+    }
+    st->prof.recs.clear();
+    *n = (int32_t)agg.size();
+    if (rc != AMDP_OK) return rc;
+    if (!out || cap < (int32_t)agg.size()) return AMDP_E_CAPACITY;
+    for (size_t i = 0; i < agg.size(); ++i) out[i] = agg[i];
+    return AMDP_OK;
+}
+
+extern "C" const char* amdp_last_hip_error(void) { return g_hip_detail; }

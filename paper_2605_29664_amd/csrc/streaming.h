@@ -36,6 +36,7 @@ __global__ __launch_bounds__(STREAM_BLOCK) void accumulate_kernel(float* __restr
 
 struct AdamScalars {
     float lr, beta1, beta2, eps, weight_decay, grad_scale;
+    float omb1, omb2;         // 1-beta1, 1-beta2, formed in double on the host
     float inv_bc1, inv_bc2;   // 1/(1-beta1^t), 1/(1-beta2^t), or 1 without bias correction
 };
 
@@ -64,8 +65,8 @@ __global__ __launch_bounds__(STREAM_BLOCK) void adam_kernel(float* __restrict__ 
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const float gh = hp.grad_scale * gg[k];
-            const float mn = hp.beta1 * mm[k] + (1.0f - hp.beta1) * gh;
-            const float vn = hp.beta2 * vv[k] + (1.0f - hp.beta2) * gh * gh;
+            const float mn = hp.beta1 * mm[k] + hp.omb1 * gh;
+            const float vn = hp.beta2 * vv[k] + hp.omb2 * gh * gh;
             const float mh = mn * hp.inv_bc1, vh = vn * hp.inv_bc2;
             const float tn = t[k] - hp.lr * (mh / (sqrtf(vh) + hp.eps) + hp.weight_decay * t[k]);
             mm[k] = mn; vv[k] = vn; t[k] = tn;
@@ -91,6 +92,31 @@ __global__ __launch_bounds__(STREAM_BLOCK) void publish_kernel(const float* __re
         for (int k = 0; k < 4; ++k) o[k] = (T)t[k];
         o4[i] = o;
     }
+}
+
+// Plain device-to-device copy and zero fill, used instead of the runtime's
+// memcpy/memset so that every byte the library moves is moved by a kernel that
+// is ordered on the stage's stream like all its other work. n16 = number of
+// 16-byte units.
+__global__ __launch_bounds__(STREAM_BLOCK) void copy16_kernel(u32x4* __restrict__ dst,
+                                                              const u32x4* __restrict__ src, long n16) {
+    const long stride = (long)gridDim.x * STREAM_BLOCK;
+    long i = (long)blockIdx.x * STREAM_BLOCK + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+__global__ __launch_bounds__(STREAM_BLOCK) void copy4_kernel(uint32_t* __restrict__ dst,
+                                                             const uint32_t* __restrict__ src, long n4b) {
+    const long stride = (long)gridDim.x * STREAM_BLOCK;
+    for (long i = (long)blockIdx.x * STREAM_BLOCK + threadIdx.x; i < n4b; i += stride) dst[i] = src[i];
+}
+__global__ __launch_bounds__(STREAM_BLOCK) void zero16_kernel(u32x4* __restrict__ dst, long n16) {
+    const long stride = (long)gridDim.x * STREAM_BLOCK;
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (long i = (long)blockIdx.x * STREAM_BLOCK + threadIdx.x; i < n16; i += stride) dst[i] = z;
 }
 
 inline int stream_grid(long n4) {

@@ -23,3 +23,8 @@ def gpu_available():
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+def pytest_collection_modifyitems(config, items):
+    # cheap tests first, full-size ones last
+    items.sort(key=lambda it: ("fullsize" in it.nodeid, "zz_" in it.nodeid))

@@ -1,0 +1,200 @@
+"""GPU parity tests: the HIP library, called through its C ABI, against the CPU
+oracle on identical seeded inputs. Tolerances are norm-wise relative errors per
+compared tensor: 2e-2 for bf16 stages, 1e-5 for fp32 stages."""
+import os
+
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import schedule as OSched
+from tests.parity import run_parity, worst_entries, GpuStage, rel_err, TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def _report(name, rep):
+    print(f"\n[{name}] ok={rep['ok']} worst={rep['worst']:.3e} tol={rep['tol']:.0e} events={rep['events']} "
+          f"sched={rep['schedule_equal']} resid={rep['residency_equal']} {rep['seconds']:.1f}s", flush=True)
+    for d in worst_entries(rep, 5):
+        print("    ", d, flush=True)
+
+
+@pytest.fixture(autouse=True)
+def _clean_env():
+    saved = {k: os.environ.get(k) for k in ("AMDP_GEMM_TR", "AMDP_GEMM_TILE")}
+    yield
+    for k, v in saved.items():
+        if v is None:
+            os.environ.pop(k, None)
+        else:
+            os.environ[k] = v
+
+
+# ---- small fp32 stages: every op, ragged shapes, generic kernels -------------
+@pytest.mark.parametrize("key", ["gpt", "bert", "lmhead"])
+@pytest.mark.parametrize("policy", [OSched.STASHED, OSched.CURRENT])
+def test_tiny_fp32(key, policy):
+    rep = run_parity(W.TINY[key], n_windows=2, policy=policy, verbose=False)
+    _report(f"tiny_{key}_p{policy}", rep)
+    assert rep["ok"], worst_entries(rep)
+
+
+def test_config1_fp32_full_schedule():
+    rep = run_parity(W.CONFIGS[1], n_windows=3, verbose=False)
+    _report("cfg1", rep)
+    assert rep["ok"], worst_entries(rep)
+
+
+def test_config1_eager_and_current():
+    rep = run_parity(W.CONFIGS[1], n_windows=2, policy=OSched.CURRENT, placement=OSched.EAGER, verbose=False)
+    _report("cfg1_eager_current", rep)
+    assert rep["ok"], worst_entries(rep)
+
+
+# ---- bf16, shapes that are not tile multiples: generic kernels in bf16 -------
+@pytest.mark.parametrize("key", ["gpt_mid", "bert_mid", "lmhead_mid"])
+def test_mid_bf16_ragged(key):
+    rep = run_parity(W.TINY[key], n_windows=1, verbose=False)
+    _report(key, rep)
+    assert rep["ok"], worst_entries(rep)
+
+
+# ---- bf16, tile-aligned shapes: the MFMA kernels ----------------------------
+@pytest.mark.parametrize("key", ["gpt_tile", "bert_tile", "lmhead_tile"])
+@pytest.mark.parametrize("tr", ["1", "0"])
+def test_tile_bf16_mfma(key, tr):
+    os.environ["AMDP_GEMM_TR"] = tr
+    rep = run_parity(W.TINY[key], n_windows=1, verbose=False)
+    _report(f"{key}_tr{tr}", rep)
+    assert rep["ok"], worst_entries(rep)
+
+
+def test_tile_bf16_generic_kernels_agree():
+    os.environ["AMDP_GEMM_TILE"] = "-1"
+    rep = run_parity(W.TINY["gpt_tile"], n_windows=1, verbose=False)
+    _report("gpt_tile_generic", rep)
+    assert rep["ok"], worst_entries(rep)
+
+
+def test_three_stashed_versions():
+    """Stress list for the stash: injection limit 3 and short windows keep three
+    older versions resident next to the current one; each backward must read
+    the version its forward used."""
+    w = W.TINY["gpt_tile"].with_(depth=16, pipelines=4, stage=8, threshold=4, stash_slots=3, lr=1e-3)
+    rep = run_parity(w, inject_limit=3, n_minibatches=40, verbose=False)
+    _report("stash3", rep)
+    assert rep["ok"], worst_entries(rep)
+
+
+def test_zero_lr_versions_bit_identical():
+    """With lr = 0 every version holds the same numbers, so stashed and current
+    backward must produce bit-identical results."""
+    w = W.TINY["gpt_tile"].with_(lr=0.0)
+    outs = []
+    for policy in (OSched.STASHED, OSched.CURRENT):
+        gpu = GpuStage(w, act_slots=w.act_slots, stash_slots=2)
+        from oracle.stage import Stage as OStage
+        theta0 = W.make_theta(w, OStage.from_workload(w).layout)
+        gpu.set_state(theta0)
+        import paper_2605_29664_amd as amdp
+        ev = amdp.amdp_schedule_generate(w.depth, w.pipelines, w.stage, w.threshold, 2 * w.threshold, 2, 0, policy)
+        log = []
+        for e in ev:
+            if e.kind == amdp.EV_F:
+                log.append(gpu.forward(e.mb, e.version, W.make_x(w, e.mb), None))
+            elif e.kind == amdp.EV_B:
+                dx, g = gpu.backward(e.mb, e.version, W.make_dy(w, e.mb))
+                log += [dx, g]
+            elif e.kind == amdp.EV_A:
+                gpu.accumulate(e.mb)
+            else:
+                gpu.update(w, 1.0 / w.threshold)
+        outs.append(log)
+        gpu.stage.close()
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+
+
+def test_run_to_run_determinism():
+    w = W.TINY["bert_tile"]
+    res = []
+    for _ in range(2):
+        gpu = GpuStage(w)
+        from oracle.stage import Stage as OStage
+        gpu.set_state(W.make_theta(w, OStage.from_workload(w).layout))
+        y = gpu.forward(0, 0, W.make_x(w, 0), W.make_valid_len(w, 0))
+        dx, g = gpu.backward(0, 0, W.make_dy(w, 0))
+        res.append((y, dx, g))
+        gpu.stage.close()
+    for a, b in zip(*res):
+        assert np.array_equal(a, b)
+
+
+def test_adam_kernel_in_isolation():
+    """Same fp32 G, m, v, theta into kernel and oracle: one update must agree
+    to fp32 rounding (norm-wise <= 1e-6)."""
+    import torch
+    from oracle import optim
+    from oracle.stage import Stage as OStage
+    w = W.TINY["gpt_tile"]
+    ost = OStage.from_workload(w)
+    rng = np.random.default_rng(7)
+    n = ost.n_params
+    theta = W.make_theta(w, ost.layout)
+    m = (1e-4 * rng.standard_normal(n)).astype(np.float32)
+    v = (1e-8 * rng.random(n)).astype(np.float32)
+    gpu = GpuStage(w)
+    gpu.set_state(theta, m, v, step=6, version=3)
+    # build a known G by one forward/backward/accumulate
+    gpu.forward(0, 3, W.make_x(w, 0), None)
+    gpu.backward(0, 3, W.make_dy(w, 0))
+    gpu.accumulate(0)
+    G = gpu.state()["G"]
+    nv = gpu.update(w, 0.25)
+    s = gpu.state()
+    th_ref, m_ref, v_ref = optim.adam_step(theta.astype(np.float64), m.astype(np.float64), v.astype(np.float64),
+                                           G.astype(np.float64), 7, w.lr, w.beta1, w.beta2, w.eps,
+                                           grad_scale=0.25)
+    assert nv == 4 and s["step"] == 7
+    assert rel_err(s["theta"], th_ref) <= 1e-6
+    assert rel_err(s["m"], m_ref) <= 1e-6 and rel_err(s["v"], v_ref) <= 1e-6
+    assert rel_err(s["theta"] - theta, th_ref - theta) <= 1e-4
+    assert np.all(s["G"] == 0.0)
+    gpu.stage.close()
+
+
+def test_state_machine_errors():
+    import paper_2605_29664_amd as amdp
+    from oracle.stage import Stage as OStage
+    w = W.TINY["gpt_tile"]
+    gpu = GpuStage(w, act_slots=2, stash_slots=1)
+    gpu.set_state(W.make_theta(w, OStage.from_workload(w).layout))
+    x, dy = W.make_x(w, 0), W.make_dy(w, 0)
+
+    def code(fn):
+        with pytest.raises(amdp.AmdpError) as ei:
+            fn()
+        return ei.value.code
+
+    assert code(lambda: gpu.backward(0, 0, dy)) == amdp.E_MB_STATE         # backward without forward
+    assert code(lambda: gpu.accumulate(0)) == amdp.E_MB_STATE
+    assert code(lambda: gpu.forward(0, 5, x, None)) == amdp.E_VERSION      # version never published
+    gpu.forward(0, 0, x, None)
+    assert code(lambda: gpu.forward(0, 0, x, None)) == amdp.E_MB_STATE     # already in flight
+    gpu.forward(1, 0, x, None)
+    assert code(lambda: gpu.forward(2, 0, x, None)) == amdp.E_NO_SLOT      # act_slots = 2
+    gpu.update(w, 1.0)                                                      # v1; v0 pinned by mb 0, 1
+    assert gpu.stage.amdp_stage_resident_versions() == [0, 1]
+    assert code(lambda: gpu.update(w, 1.0)) == amdp.E_STASH_FULL           # both slots still needed
+    gpu.backward(0, 0, dy)
+    assert code(lambda: gpu.backward(1, 0, dy)) == amdp.E_MB_STATE         # staging buffer occupied
+    assert code(lambda: gpu.update(w, 1.0)) == amdp.E_MB_STATE             # gradient not yet accumulated
+    gpu.accumulate(0)
+    gpu.backward(1, 0, dy)
+    gpu.accumulate(1)
+    assert gpu.stage.amdp_stage_resident_versions() == [1]                  # v0 dropped with its last reader
+    assert code(lambda: gpu.forward(3, 0, x, None)) == amdp.E_VERSION
+    gpu.update(w, 1.0)
+    assert gpu.stage.amdp_stage_resident_versions() == [2]
+    gpu.stage.close()

@@ -13,7 +13,7 @@ import workloads as W
 from oracle import stage as OS
 from oracle.stage import Stage
 
-torch.set_default_dtype(torch.float64)
+F64 = torch.float64
 
 
 def _setup(key, mb=0):
@@ -78,7 +78,7 @@ def torch_stage(w, theta_t, x_t, aux):
 def test_forward_matches_library_ops(key):
     w, st, theta, x, aux, _ = _setup(key)
     out, _ = st.forward(theta, x, aux)
-    ref = torch_stage(w, torch.tensor(theta), torch.tensor(x), aux).detach().numpy()
+    ref = torch_stage(w, torch.tensor(theta, dtype=F64), torch.tensor(x, dtype=F64), aux).detach().numpy()
     assert np.allclose(out, ref, rtol=1e-11, atol=1e-12)
 
 
@@ -87,13 +87,13 @@ def test_backward_matches_autograd(key):
     w, st, theta, x, aux, dy = _setup(key)
     _, saved = st.forward(theta, x, aux)
     dx, g = st.backward(theta, saved, dy)
-    tt = torch.tensor(theta, requires_grad=True)
-    xt = torch.tensor(x, requires_grad=True)
+    tt = torch.tensor(theta, dtype=F64, requires_grad=True)
+    xt = torch.tensor(x, dtype=F64, requires_grad=True)
     out = torch_stage(w, tt, xt, aux)
     if w.has_lm_head:
         out.backward()
     else:
-        out.backward(torch.tensor(dy))
+        out.backward(torch.tensor(dy, dtype=F64))
     assert np.allclose(dx, xt.grad.numpy(), rtol=1e-9, atol=1e-12)
     assert np.allclose(g, tt.grad.numpy(), rtol=1e-9, atol=1e-12)
 
