@@ -1,6 +1,6 @@
 // bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), fp32
-// accumulation. Tiles are staged through LDS; one workgroup = 4 wavefronts of
-// 64 lanes arranged 2x2 over the BM x BN output tile.
+// accumulation. Tiles are staged through LDS (double buffered); one workgroup
+// = 4 wavefronts of 64 lanes arranged 2x2 over the BM x BN output tile.
 //
 // Operand storage, per template flag:
 //   A_KM = false : A is [M][K], k contiguous        (activations, dY)
@@ -21,67 +21,91 @@
 namespace amdp {
 
 constexpr int MF_BK = 64;
-constexpr int MF_PAD = 8;   // bf16 elements of padding per LDS row
+
+// LDS pointers carry their address space so that every access is a ds_*
+// instruction with an immediate offset.
+typedef __attribute__((address_space(3))) unsigned char lds_u8;
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) bf16 lds_bf16;
+typedef __attribute__((address_space(3))) float lds_f32;
+typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
 
 template <int R, bool KM>
 struct OperandTile {
-    // LDS footprint in elements
+    // LDS rows are padded so that consecutive rows start 16 bytes (k-contiguous
+    // tile: 128-bit reads of 16 rows) or 32 bytes (transposing reads: 4 rows x
+    // 32 bytes per 16-lane group) further round the banks.
+    static constexpr int PAD = KM ? 16 : 8;
     static constexpr int ROWS = KM ? MF_BK : R;
-    static constexpr int COLS = (KM ? R : MF_BK) + MF_PAD;
-    static constexpr int ELEMS = ROWS * COLS;
-    static constexpr int VEC_PER_THREAD = R / 32;   // 16-byte vectors each thread moves per tile
+    static constexpr int COLS = (KM ? R : MF_BK) + PAD;
+    static constexpr int BYTES = ROWS * COLS * 2;
+    static constexpr int NV = R / 32;               // 16-byte vectors per thread per tile
+    static constexpr int VPR = KM ? R / 8 : 8;      // vectors per LDS row
+    static constexpr int ROWS_PER_PASS = 256 / VPR; // rows covered by the 256 threads in one pass
 
-    // global -> registers. `p` points at element (row r0, k = 0) of the operand.
-    // rs: stride between consecutive rows (m or n), ks: stride between consecutive k.
-    __device__ static __forceinline__ void load(u32x4 (&reg)[VEC_PER_THREAD], const bf16* p, long rs,
-                                                long ks, int k0, int tid) {
-#pragma unroll
-        for (int i = 0; i < VEC_PER_THREAD; ++i) {
-            const int v = tid + i * 256;
-            if constexpr (!KM) {
-                const int row = v / 8, kc = v % 8;
-                reg[i] = *(const u32x4*)(p + (long)row * rs + (k0 + kc * 8));
-            } else {
-                const int krow = v / (R / 8), c = v % (R / 8);
-                reg[i] = *(const u32x4*)(p + (long)(k0 + krow) * ks + c * 8);
-            }
-        }
+    // Byte offset, inside the operand, of the first vector this thread loads
+    // (row stride rs and k stride ks in elements).
+    __device__ static __forceinline__ long thread_goff(int tid, long rs, long ks) {
+        const int row = tid / VPR, c = tid % VPR;
+        return KM ? ((long)row * ks + c * 8) * 2 : ((long)row * rs + c * 8) * 2;
     }
-    __device__ static __forceinline__ void store(const u32x4 (&reg)[VEC_PER_THREAD], bf16* lds, int tid) {
-#pragma unroll
-        for (int i = 0; i < VEC_PER_THREAD; ++i) {
-            const int v = tid + i * 256;
-            if constexpr (!KM) {
-                const int row = v / 8, kc = v % 8;
-                *(u32x4*)(lds + row * COLS + kc * 8) = reg[i];
-            } else {
-                const int krow = v / (R / 8), c = v % (R / 8);
-                *(u32x4*)(lds + krow * COLS + c * 8) = reg[i];
-            }
-        }
+    // Byte distance between the vectors of consecutive passes.
+    __device__ static __forceinline__ long pass_gstride(long rs, long ks) {
+        return (KM ? (long)ROWS_PER_PASS * ks : (long)ROWS_PER_PASS * rs) * 2;
     }
-    // fragment for the 32-wide sub-tile starting at row `r`, k-step kk (16 k each)
+    // Byte distance between consecutive k-tiles.
+    __device__ static __forceinline__ long ktile_gstride(long ks) { return (KM ? (long)MF_BK * ks : MF_BK) * 2; }
+    __device__ static __forceinline__ int thread_loff(int tid) {
+        const int row = tid / VPR, c = tid % VPR;
+        return (row * COLS + c * 8) * 2;
+    }
+    static constexpr int PASS_LSTRIDE = ROWS_PER_PASS * COLS * 2;
+
+    __device__ static __forceinline__ void load(u32x4 (&reg)[NV], const char* p, long pass_stride) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) reg[i] = *(const u32x4*)(p + i * pass_stride);
+    }
+    __device__ static __forceinline__ void store(const u32x4 (&reg)[NV], lds_u8* p) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) *(lds_u32x4*)(p + i * PASS_LSTRIDE) = reg[i];
+    }
+
+    // Per-lane byte offset of this lane's fragment data inside the tile, for the
+    // 32-wide sub-tile at row 0 and k-step 0.
     template <bool TR>
-    __device__ static __forceinline__ bf16x8 frag(const bf16* lds, int r, int kk, int lane) {
+    __device__ static __forceinline__ int lane_foff(int lane) {
         if constexpr (!KM) {
-            return *(const bf16x8*)(lds + (r + (lane & 31)) * COLS + kk * 16 + 8 * (lane >> 5));
+            return ((lane & 31) * COLS + 8 * (lane >> 5)) * 2;
         } else if constexpr (TR) {
-            // 16-lane group q: columns r + 16*(q&1) .. +15, k = kk*16 + 8*(q>>1) .. +7.
-            // Lane i of the group addresses row k + i/4 (+4 for the second read),
-            // columns 4*(i%4)..+3; the read hands lane j the 4 k-values of column j.
+            // 16-lane group q: columns 16*(q&1) .. +15, k = 8*(q>>1) .. +7. Lane i of
+            // the group addresses row k + i/4 (+4 for the second read), columns
+            // 4*(i%4)..+3; the read hands lane j the 4 k-values of column j.
             const int q = lane >> 4, i = lane & 15;
-            const bf16* p = lds + (kk * 16 + 8 * (q >> 1) + (i >> 2)) * COLS + r + 16 * (q & 1) + 4 * (i & 3);
-            typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
-            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * COLS));
+            return ((8 * (q >> 1) + (i >> 2)) * COLS + 16 * (q & 1) + 4 * (i & 3)) * 2;
+        } else {
+            return (8 * (lane >> 5) * COLS + (lane & 31)) * 2;
+        }
+    }
+    // Fragment of the sub-tile at row r0 (multiple of 32), k-step kk (16 k each);
+    // r0 and kk are compile-time so the whole offset folds into the instruction.
+    template <bool TR>
+    __device__ static __forceinline__ bf16x8 frag(lds_u8* base, int r0, int kk) {
+        if constexpr (!KM) {
+            return *(lds_bf16x8*)(base + (r0 * COLS + kk * 16) * 2);
+        } else if constexpr (TR) {
+            lds_u8* p = base + (kk * 16 * COLS + r0) * 2;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * COLS * 2));
             typedef __attribute__((ext_vector_type(8))) short s16x8;
-            s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             return __builtin_bit_cast(bf16x8, both);
         } else {
             bf16x8 out;
-            const bf16* p = lds + (kk * 16 + 8 * (lane >> 5)) * COLS + r + (lane & 31);
+            lds_u8* p = base + (kk * 16 * COLS + r0) * 2;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) out[j] = p[j * COLS];
+            for (int j = 0; j < 8; ++j) out[j] = *(lds_bf16*)(p + j * COLS * 2);
             return out;
         }
     }
@@ -93,10 +117,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     constexpr int TM = WM / 32, TN = WN / 32;     // 32x32 MFMA tiles per wave
     using TA = OperandTile<BM, A_KM>;
     using TB = OperandTile<BN, B_KM>;
+    constexpr int STAGE = TA::BYTES + TB::BYTES;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16* smem = (bf16*)smem_raw;
-    bf16* ldsA[2] = {smem, smem + TA::ELEMS + TB::ELEMS};
-    bf16* ldsB[2] = {smem + TA::ELEMS, smem + 2 * TA::ELEMS + TB::ELEMS};
+    lds_u8* lds = (lds_u8*)smem_raw;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -122,9 +145,21 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 
     const int z = blockIdx.z;
     const long zo = z / g.batch_inner, zi = z % g.batch_inner;
-    const bf16* A = (const bf16*)g.A + zo * g.a_bo + zi * g.a_bi + (long)m0 * g.a_rs;
-    const bf16* B = (const bf16*)g.B + zo * g.b_bo + zi * g.b_bi + (long)n0 * g.b_cs;
     const long c_off = zo * g.c_bo + zi * g.c_bi;
+
+    // global source pointers of this thread's first vector, advanced per k-tile
+    const char* pa = (const char*)((const bf16*)g.A + zo * g.a_bo + zi * g.a_bi + (long)m0 * g.a_rs + (long)k_lo * g.a_cs) +
+                     TA::thread_goff(tid, g.a_rs, g.a_cs);
+    const char* pb = (const char*)((const bf16*)g.B + zo * g.b_bo + zi * g.b_bi + (long)n0 * g.b_cs + (long)k_lo * g.b_rs) +
+                     TB::thread_goff(tid, g.b_cs, g.b_rs);
+    const long a_pass = TA::pass_gstride(g.a_rs, g.a_cs), b_pass = TB::pass_gstride(g.b_cs, g.b_rs);
+    const long a_step = TA::ktile_gstride(g.a_cs), b_step = TB::ktile_gstride(g.b_rs);
+
+    // LDS addresses: where this thread stores, where this lane reads fragments
+    lds_u8* sa = lds + TA::thread_loff(tid);
+    lds_u8* sb = lds + TA::BYTES + TB::thread_loff(tid);
+    lds_u8* fa = lds + TA::template lane_foff<TR>(lane) + (wm * WM) * (A_KM ? 2 : TA::COLS * 2);
+    lds_u8* fb = lds + TA::BYTES + TB::template lane_foff<TR>(lane) + (wn * WN) * (B_KM ? 2 : TB::COLS * 2);
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -134,39 +169,41 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    u32x4 ra[TA::VEC_PER_THREAD], rb[TB::VEC_PER_THREAD];
+    u32x4 ra[TA::NV], rb[TB::NV];
     const int nk = (k_hi - k_lo) / MF_BK;
     if (nk > 0) {
-        TA::load(ra, A, g.a_rs, g.a_cs, k_lo, tid);
-        TB::load(rb, B, g.b_cs, g.b_rs, k_lo, tid);
-        TA::store(ra, ldsA[0], tid);
-        TB::store(rb, ldsB[0], tid);
+        TA::load(ra, pa, a_pass);
+        TB::load(rb, pb, b_pass);
+        TA::store(ra, sa);
+        TB::store(rb, sb);
     }
     __syncthreads();
 
     for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
+        const int cur = (kt & 1) * STAGE, nxt = STAGE - cur;
         const bool more = kt + 1 < nk;
         if (more) {
-            TA::load(ra, A, g.a_rs, g.a_cs, k_lo + (kt + 1) * MF_BK, tid);
-            TB::load(rb, B, g.b_cs, g.b_rs, k_lo + (kt + 1) * MF_BK, tid);
+            pa += a_step;
+            pb += b_step;
+            TA::load(ra, pa, a_pass);
+            TB::load(rb, pb, b_pass);
         }
 #pragma unroll
         for (int kk = 0; kk < MF_BK / 16; ++kk) {
-            bf16x8 fa[TM], fb[TN];
+            bf16x8 va[TM], vb[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = TA::template frag<TR>(ldsA[cur], wm * WM + i * 32, kk, lane);
+            for (int i = 0; i < TM; ++i) va[i] = TA::template frag<TR>(fa + cur, i * 32, kk);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = TB::template frag<TR>(ldsB[cur], wn * WN + j * 32, kk, lane);
+            for (int j = 0; j < TN; ++j) vb[j] = TB::template frag<TR>(fb + cur, j * 32, kk);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i], vb[j], acc[i][j], 0, 0, 0);
         }
         if (more) {
-            TA::store(ra, ldsA[cur ^ 1], tid);
-            TB::store(rb, ldsB[cur ^ 1], tid);
+            TA::store(ra, sa + nxt);
+            TB::store(rb, sb + nxt);
         }
         __syncthreads();
     }
@@ -176,7 +213,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     // consecutive columns and the wave writes whole row segments.
     void* C = g.epi.out_f32 ? (void*)((float*)g.C + c_off) : (void*)((bf16*)g.C + c_off);
     constexpr int SW = WN + 4;                     // strip row stride in floats
-    float* strip = (float*)smem_raw + wave * (32 * SW);
+    lds_f32* strip = (lds_f32*)lds + wave * (32 * SW);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         __syncthreads();                           // previous strip fully read (first pass: main loop done)
@@ -191,8 +228,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
             const int c = lane + 64 * it;
             const int row = c / CPR, cc = c % CPR;
             float v8[8];
-            const f32x4 lo = *(const f32x4*)(strip + row * SW + cc * 8);
-            const f32x4 hi = *(const f32x4*)(strip + row * SW + cc * 8 + 4);
+            const f32x4 lo = *(lds_f32x4*)(strip + row * SW + cc * 8);
+            const f32x4 hi = *(lds_f32x4*)(strip + row * SW + cc * 8 + 4);
 #pragma unroll
             for (int k = 0; k < 4; ++k) { v8[k] = lo[k]; v8[4 + k] = hi[k]; }
             const long m = m0 + wm * WM + i * 32 + row;
@@ -204,7 +241,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 
 template <int BM, int BN, bool A_KM, bool B_KM>
 constexpr size_t mfma_lds_bytes() {
-    return 2 * (size_t)(OperandTile<BM, A_KM>::ELEMS + OperandTile<BN, B_KM>::ELEMS) * sizeof(bf16);
+    return 2 * (size_t)(OperandTile<BM, A_KM>::BYTES + OperandTile<BN, B_KM>::BYTES);
 }
 
 // True when the problem satisfies every assumption of gemm_mfma_kernel<BM,BN,...>.
@@ -229,6 +266,7 @@ inline bool mfma_shape_ok(const GemmArgs& g, bool a_km, bool b_km) {
 template <int BM, int BN, bool A_KM, bool B_KM, bool TR>
 inline hipError_t launch_gemm_mfma_inst(const GemmArgs& g, hipStream_t st) {
     constexpr size_t lds = mfma_lds_bytes<BM, BN, A_KM, B_KM>();
+    static_assert(lds <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
     auto kern = gemm_mfma_kernel<BM, BN, A_KM, B_KM, TR>;
     static bool attr_set = false;
     if (!attr_set) {
