@@ -21,6 +21,9 @@
 namespace amdp {
 
 constexpr int MF_BK = 64;
+#ifndef AMDP_GEMM_SCHED
+#define AMDP_GEMM_SCHED 1
+#endif
 
 // LDS pointers carry their address space so that every access is a ds_*
 // instruction with an immediate offset.
@@ -179,32 +182,80 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     }
     __syncthreads();
 
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = (kt & 1) * STAGE, nxt = STAGE - cur;
-        const bool more = kt + 1 < nk;
-        if (more) {
-            pa += a_step;
-            pb += b_step;
-            TA::load(ra, pa, a_pass);
-            TB::load(rb, pb, b_pass);
-        }
+    constexpr int KSTEPS = MF_BK / 16;
+    constexpr int NDS = TM * (A_KM && TR ? 2 : 1) + TN * (B_KM && TR ? 2 : 1);   // LDS reads per k-step
+    constexpr int NMF = TM * TN;                                                 // MFMAs per k-step
+
+    // One k-tile of matrix work out of the LDS stage at byte offset `cur`.
+    // Fragments are double buffered in registers: the LDS reads of k-step kk+1
+    // are in flight while the matrix cores work on k-step kk.
+    auto compute_tile = [&](int cur) {
+        bf16x8 va[2][TM], vb[2][TN];
 #pragma unroll
-        for (int kk = 0; kk < MF_BK / 16; ++kk) {
-            bf16x8 va[TM], vb[TN];
+        for (int i = 0; i < TM; ++i) va[0][i] = TA::template frag<TR>(fa + cur, i * 32, 0);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) va[i] = TA::template frag<TR>(fa + cur, i * 32, kk);
+        for (int j = 0; j < TN; ++j) vb[0][j] = TB::template frag<TR>(fb + cur, j * 32, 0);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) vb[j] = TB::template frag<TR>(fb + cur, j * 32, kk);
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            const int c = kk & 1, n = c ^ 1;
+            if (kk + 1 < KSTEPS) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) va[n][i] = TA::template frag<TR>(fa + cur, i * 32, kk + 1);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) vb[n][j] = TB::template frag<TR>(fb + cur, j * 32, kk + 1);
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i], vb[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[c][i], vb[c][j], acc[i][j], 0, 0, 0);
         }
-        if (more) {
-            TA::store(ra, sa + nxt);
-            TB::store(rb, sb + nxt);
+    };
+
+    // Steady state: while tile kt is multiplied, tile kt+1 travels global ->
+    // registers -> the other LDS stage. The loop body is one basic block; the
+    // scheduling directives at its end spread the memory instructions between
+    // the matrix instructions instead of letting them bunch up:
+    //   k-step 0: global loads of the next tile and LDS reads of k-step 1
+    //   k-steps 1..: LDS reads of the following k-step
+    //   last k-step: LDS writes of the next tile (its global loads are ~3 k-steps old)
+    for (int kt = 0; kt + 1 < nk; ++kt) {
+        const int cur = (kt & 1) * STAGE, nxt = STAGE - cur;
+        pa += a_step;
+        pb += b_step;
+        TA::load(ra, pa, a_pass);
+        TB::load(rb, pb, b_pass);
+        compute_tile(cur);
+        TA::store(ra, sa + nxt);
+        TB::store(rb, sb + nxt);
+#if AMDP_GEMM_SCHED
+        __builtin_amdgcn_sched_group_barrier(0x100, NDS, 0);
+        constexpr int NVM = TA::NV + TB::NV;
+#pragma unroll
+        for (int t = 0; t < NMF; ++t) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (t < NVM) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            if (t < NDS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
+        if (NVM > NMF) __builtin_amdgcn_sched_group_barrier(0x020, NVM - NMF, 0);
+#pragma unroll
+        for (int kk = 1; kk + 1 < KSTEPS; ++kk)
+#pragma unroll
+            for (int t = 0; t < NMF; ++t) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (t < NDS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+#pragma unroll
+        for (int t = 0; t < NMF; ++t) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (t < NVM) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        }
+        if (NVM > NMF) __builtin_amdgcn_sched_group_barrier(0x200, NVM - NMF, 0);
+#endif
+        __syncthreads();
+    }
+    if (nk > 0) {
+        compute_tile(((nk - 1) & 1) * STAGE);
         __syncthreads();
     }
 

@@ -128,7 +128,9 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
 }
 
 // ----------------------------------------------------------- column reductions
-// Stage 1: thread = column, block row = a chunk of rows.
+// Stage 1: a block owns 64*VEC consecutive columns and one chunk of rows; its 4
+// waves take rows round-robin, every lane keeps VEC column sums in registers
+// (16-byte loads along the row), the waves are combined through LDS.
 //   LN = false: partial[rc][c]      = sum_r dy[r][c]
 //   LN = true : partial[rc][c]      = sum_r dy[r][c] * xhat[r][c]      (dgamma)
 //               partial[rc][C + c]  = sum_r dy[r][c]                    (dbeta)
@@ -138,31 +140,62 @@ __global__ __launch_bounds__(256) void colreduce_partial_kernel(const T* __restr
                                                                const float* __restrict__ stats,
                                                                float* __restrict__ partial, int N, int C,
                                                                int rows_per_chunk) {
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= C) return;
+    constexpr int V = Vec<T>::N;
+    __shared__ float red[2][4][64 * V];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c0 = (blockIdx.x * 64 + lane) * V;
+    const bool live = c0 < C;                       // C is a multiple of V
     const int r0 = blockIdx.y * rows_per_chunk, r1 = min(N, r0 + rows_per_chunk);
-    float s = 0.f, sg = 0.f;
-    for (int r = r0; r < r1; ++r) {
-        const float d = to_f32(dy[(long)r * C + c]);
-        s += d;
-        if constexpr (LN) sg += d * (to_f32(x[(long)r * C + c]) - stats[2 * r]) * stats[2 * r + 1];
+    float s[V], sg[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) { s[i] = 0.f; sg[i] = 0.f; }
+    if (live) {
+        for (int r = r0 + wave; r < r1; r += 4) {
+            float d[V];
+            load_vec<T>(dy + (long)r * C + c0, d);
+            if constexpr (LN) {
+                float a[V];
+                load_vec<T>(x + (long)r * C + c0, a);
+                const float mean = stats[2 * r], rstd = stats[2 * r + 1];
+#pragma unroll
+                for (int i = 0; i < V; ++i) sg[i] += d[i] * (a[i] - mean) * rstd;
+            }
+#pragma unroll
+            for (int i = 0; i < V; ++i) s[i] += d[i];
+        }
     }
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        red[0][wave][lane * V + i] = s[i];
+        if constexpr (LN) red[1][wave][lane * V + i] = sg[i];
+    }
+    __syncthreads();
     const long width = LN ? 2 * (long)C : C;
-    if constexpr (LN) {
-        partial[blockIdx.y * width + c] = sg;
-        partial[blockIdx.y * width + C + c] = s;
-    } else {
-        partial[blockIdx.y * width + c] = s;
+    for (int j = threadIdx.x; j < 64 * V; j += 256) {
+        const int c = blockIdx.x * 64 * V + j;
+        if (c >= C) continue;
+        const float t = red[0][0][j] + red[0][1][j] + red[0][2][j] + red[0][3][j];
+        if constexpr (LN) {
+            partial[blockIdx.y * width + c] = red[1][0][j] + red[1][1][j] + red[1][2][j] + red[1][3][j];
+            partial[blockIdx.y * width + C + c] = t;
+        } else {
+            partial[blockIdx.y * width + c] = t;
+        }
     }
 }
-// Stage 2: out[c] = sum over chunks, in chunk order.
+// Stage 2: out[c] = sum over chunks. A block owns 64 columns; its 4 groups of
+// 64 threads each sum every 4th chunk, then the groups are added in fixed order.
 __global__ __launch_bounds__(256) void colreduce_final_kernel(const float* __restrict__ partial,
                                                              float* __restrict__ out, int width, int chunks) {
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= width) return;
+    __shared__ float red[4][64];
+    const int j = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + j;
     float s = 0.f;
-    for (int k = 0; k < chunks; ++k) s += partial[(long)k * width + c];
-    out[c] = s;
+    if (c < width)
+        for (int k = grp; k < chunks; k += 4) s += partial[(long)k * width + c];
+    red[grp][j] = s;
+    __syncthreads();
+    if (grp == 0 && c < width) out[c] = (red[0][j] + red[1][j]) + (red[2][j] + red[3][j]);
 }
 
 // -------------------------------------------------------------------- softmax

@@ -353,15 +353,19 @@ int ln_bwd(amdp_stage* st, const void* dy, const void* x, const float* stats, co
 template <class T, bool LN>
 int colreduce(amdp_stage* st, const void* dy, const void* x, const float* stats, float* out, int C) {
     const Dims& d = st->d;
-    const int rpc = std::max(16, (d.N + st->w.partial_chunks - 1) / st->w.partial_chunks);
-    const int chunks = (d.N + rpc - 1) / rpc;
+    // enough row chunks to put ~4 blocks on every compute unit, at least 8 rows each
+    constexpr int V = Vec<T>::N;
+    const int col_blocks = (C + 64 * V - 1) / (64 * V);
+    int chunks = std::min(st->w.partial_chunks, std::max(1, 512 / col_blocks));
+    int rpc = std::max(8, (d.N + chunks - 1) / chunks);
+    chunks = (d.N + rpc - 1) / rpc;
     float* partial = st->at<float>(st->w.partial);
     ProfScope ps(st, LN ? "colreduce_ln" : "colreduce_bias", 0.0, (double)d.N * C * sizeof(T) * (LN ? 2 : 1));
-    hipLaunchKernelGGL((colreduce_partial_kernel<T, LN>), dim3((C + 255) / 256, chunks), dim3(256), 0,
+    hipLaunchKernelGGL((colreduce_partial_kernel<T, LN>), dim3(col_blocks, chunks), dim3(256), 0,
                        st->stream, (const T*)dy, (const T*)x, stats, partial, d.N, C, rpc);
     TRY(after_launch());
     const int width = LN ? 2 * C : C;
-    hipLaunchKernelGGL(colreduce_final_kernel, dim3((width + 255) / 256), dim3(256), 0, st->stream, partial,
+    hipLaunchKernelGGL(colreduce_final_kernel, dim3((width + 63) / 64), dim3(256), 0, st->stream, partial,
                        out, width, chunks);
     return after_launch();
 }
