@@ -104,7 +104,11 @@ struct SlotLayout {
 };
 struct Carve {
     size_t theta, m, v, G, g, versions, version_bytes, act, slot_bytes;
-    size_t buf[4], dqkv, dffn, dP, partial, row_loss, total;
+    // backward scratch: one set per layer so that gradient leaves running on the
+    // side stream never see their inputs overwritten by the main chain
+    struct BwdScratch { size_t t_a, t_b, t_c, dffn, dqkv, dxout; };
+    std::vector<BwdScratch> bw;
+    size_t lm_dz, lm_dy, dO, dP, partial, row_loss, total;
     int partial_chunks;
     SlotLayout slot;
 };
@@ -138,9 +142,15 @@ void carve(const Dims& d, const amdp_stage_config_t& c, Carve* w) {
     }
     w->slot_bytes = w->slot.bytes;
     w->act = take(w->slot_bytes * (size_t)c.act_slots);
-    for (int i = 0; i < 4; ++i) w->buf[i] = take(ND);
-    w->dqkv = take(3 * ND);
-    w->dffn = take(NF);
+    w->bw.resize(d.L);
+    for (int l = 0; l < d.L; ++l) {
+        Carve::BwdScratch& b = w->bw[l];
+        b.t_a = take(ND); b.t_b = take(ND); b.t_c = take(ND);
+        b.dffn = take(NF); b.dqkv = take(3 * ND); b.dxout = take(ND);
+    }
+    w->lm_dz = take(d.lm ? ND : 0);
+    w->lm_dy = take(d.lm ? ND : 0);
+    w->dO = take(ND);
     w->dP = take(PP);
     w->partial_chunks = 64;
     const size_t maxw = (size_t)std::max(std::max(3 * d.D, d.F), 2 * d.D);
@@ -183,6 +193,16 @@ struct amdp_stage {
     bool use_tr = true;
     int force_tile = 0;
     Profiler prof;
+    // Launch target of the helper functions: the caller's stream, or the side
+    // stream while a gradient leaf (dW GEMM, bias / LayerNorm column sums) is
+    // being enqueued. Leaves are off the dX critical path and fill the compute
+    // units the chain's small GEMMs leave idle.
+    hipStream_t launch = nullptr;
+    hipStream_t side = nullptr;
+    hipEvent_t events[16] = {};
+    int ev_next = 0;
+    bool overlap = true;
+    hipEvent_t next_event() { ev_next = (ev_next + 1) % 16; return events[ev_next]; }
 
     template <class P = void> P* at(size_t off) const { return (P*)(base + off); }
     char* version_ptr(int slot) const { return base + w.versions + (size_t)slot * w.version_bytes; }
@@ -253,12 +273,12 @@ struct ProfScope {
         if (!st->prof.on) return;
         ProfRecord r{st->prof.id_of(name), nullptr, nullptr, flops, bytes};
         if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
-        hipEventRecord(r.start, st->stream);
+        hipEventRecord(r.start, st->launch);
         st->prof.recs.push_back(r);
         idx = (int)st->prof.recs.size() - 1;
     }
     ~ProfScope() {
-        if (idx >= 0) hipEventRecord(st->prof.recs[idx].stop, st->stream);
+        if (idx >= 0) hipEventRecord(st->prof.recs[idx].stop, st->launch);
     }
 };
 
@@ -290,19 +310,19 @@ int gemm_bf16_layout(amdp_stage* st, const GemmArgs& g) {
     ProfScope ps(st, name, gemm_flops(g), 0.0);
     switch (tile) {
         case 256:
-            e = tr ? launch_gemm_mfma_inst<256, 256, A_KM, B_KM, true>(g, st->stream)
-                   : launch_gemm_mfma_inst<256, 256, A_KM, B_KM, false>(g, st->stream);
+            e = tr ? launch_gemm_mfma_inst<256, 256, A_KM, B_KM, true>(g, st->launch)
+                   : launch_gemm_mfma_inst<256, 256, A_KM, B_KM, false>(g, st->launch);
             break;
         case 128:
-            e = tr ? launch_gemm_mfma_inst<128, 128, A_KM, B_KM, true>(g, st->stream)
-                   : launch_gemm_mfma_inst<128, 128, A_KM, B_KM, false>(g, st->stream);
+            e = tr ? launch_gemm_mfma_inst<128, 128, A_KM, B_KM, true>(g, st->launch)
+                   : launch_gemm_mfma_inst<128, 128, A_KM, B_KM, false>(g, st->launch);
             break;
         case 64:
-            e = tr ? launch_gemm_mfma_inst<128, 64, A_KM, B_KM, true>(g, st->stream)
-                   : launch_gemm_mfma_inst<128, 64, A_KM, B_KM, false>(g, st->stream);
+            e = tr ? launch_gemm_mfma_inst<128, 64, A_KM, B_KM, true>(g, st->launch)
+                   : launch_gemm_mfma_inst<128, 64, A_KM, B_KM, false>(g, st->launch);
             break;
         default:
-            e = launch_gemm_simple<bf16>(g, st->stream);
+            e = launch_gemm_simple<bf16>(g, st->launch);
     }
     return hip_ok(e, name) ? AMDP_OK : AMDP_E_HIP;
 }
@@ -320,7 +340,7 @@ int gemm(amdp_stage* st, GemmLayout lay, GemmArgs g, long lda, long ldb) {
     if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return AMDP_OK;
     if (!st->d.bf) {
         ProfScope ps(st, "gemm_generic_fp32", gemm_flops(g), 0.0);
-        return hip_ok(launch_gemm_simple<float>(g, st->stream), "gemm_generic_fp32") ? AMDP_OK : AMDP_E_HIP;
+        return hip_ok(launch_gemm_simple<float>(g, st->launch), "gemm_generic_fp32") ? AMDP_OK : AMDP_E_HIP;
     }
     switch (lay) {
         case G_NN: return gemm_bf16_layout<false, true>(st, g);
@@ -335,7 +355,7 @@ int ln_fwd(amdp_stage* st, const void* x, const void* gamma, const void* beta, v
     const Dims& d = st->d;
     ProfScope ps(st, "layernorm_fwd", 0.0, (double)d.N * d.D * sizeof(T) * 2);
     hipLaunchKernelGGL(ln_fwd_kernel<T>, dim3((d.N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0,
-                       st->stream, (const T*)x, (const T*)gamma, (const T*)beta, (T*)y, stats, d.N, d.D,
+                       st->launch, (const T*)x, (const T*)gamma, (const T*)beta, (T*)y, stats, d.N, d.D,
                        st->cfg.ln_eps);
     return after_launch();
 }
@@ -345,7 +365,7 @@ int ln_bwd(amdp_stage* st, const void* dy, const void* x, const float* stats, co
     const Dims& d = st->d;
     ProfScope ps(st, "layernorm_bwd", 0.0, (double)d.N * d.D * sizeof(T) * (res ? 4 : 3));
     hipLaunchKernelGGL(ln_bwd_kernel<T>, dim3((d.N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0,
-                       st->stream, (const T*)dy, (const T*)x, stats, (const T*)gamma, (const T*)res, (T*)dx,
+                       st->launch, (const T*)dy, (const T*)x, stats, (const T*)gamma, (const T*)res, (T*)dx,
                        d.N, d.D);
     return after_launch();
 }
@@ -362,10 +382,10 @@ int colreduce(amdp_stage* st, const void* dy, const void* x, const float* stats,
     float* partial = st->at<float>(st->w.partial);
     ProfScope ps(st, LN ? "colreduce_ln" : "colreduce_bias", 0.0, (double)d.N * C * sizeof(T) * (LN ? 2 : 1));
     hipLaunchKernelGGL((colreduce_partial_kernel<T, LN>), dim3(col_blocks, chunks), dim3(256), 0,
-                       st->stream, (const T*)dy, (const T*)x, stats, partial, d.N, C, rpc);
+                       st->launch, (const T*)dy, (const T*)x, stats, partial, d.N, C, rpc);
     TRY(after_launch());
     const int width = LN ? 2 * C : C;
-    hipLaunchKernelGGL(colreduce_final_kernel, dim3((width + 63) / 64), dim3(256), 0, st->stream, partial,
+    hipLaunchKernelGGL(colreduce_final_kernel, dim3((width + 63) / 64), dim3(256), 0, st->launch, partial,
                        out, width, chunks);
     return after_launch();
 }
@@ -395,7 +415,7 @@ int attention_fwd(amdp_stage* st, const void* qkv_, void* P_, void* o_, const in
     {
     ProfScope ps(st, "softmax_fwd", 0.0, (double)rows * d.s * sizeof(T) * (d.causal ? 1.5 : 2.0));
     hipLaunchKernelGGL(softmax_fwd_kernel<T>, dim3((unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK)),
-                       dim3(256), 0, st->stream, (T*)P_, rows, d.s, 1.0f / sqrtf((float)d.dh),
+                       dim3(256), 0, st->launch, (T*)P_, rows, d.s, 1.0f / sqrtf((float)d.dh),
                        d.causal ? 1 : 0, valid, d.H);
     }
     TRY(after_launch());
@@ -443,7 +463,7 @@ int attention_bwd(amdp_stage* st, const void* dO_, const void* qkv_, const void*
     {
     ProfScope ps(st, "softmax_bwd", 0.0, (double)rows * d.s * sizeof(T) * (d.causal ? 2.0 : 3.0));
     hipLaunchKernelGGL(softmax_bwd_kernel<T>, dim3((unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK)),
-                       dim3(256), 0, st->stream, (const T*)P_, (T*)dP_, rows, d.s, 1.0f / sqrtf((float)d.dh),
+                       dim3(256), 0, st->launch, (const T*)P_, (T*)dP_, rows, d.s, 1.0f / sqrtf((float)d.dh),
                        d.causal ? 1 : 0, valid, d.H);
     }
     TRY(after_launch());
@@ -500,7 +520,7 @@ int forward_impl(amdp_stage* st, int aslot, int vslot, const void* X, const int3
     const int32_t* valid = (!d.causal && !d.lm) ? aux : nullptr;
     {
         ProfScope ps(st, "copy_input", 0.0, 2.0 * (double)ND);
-        TRY(device_copy(st->stream, S + st->w.slot.layers[0].xin, X, ND));
+        TRY(device_copy(st->launch, S + st->w.slot.layers[0].xin, X, ND));
     }
     for (int l = 0; l < d.L; ++l) {
         const LayerAct& a = st->w.slot.layers[l];
@@ -537,13 +557,37 @@ int forward_impl(amdp_stage* st, int aslot, int vslot, const void* X, const int3
         float* row_loss = st->at<float>(st->w.row_loss);
         ProfScope ps(st, "cross_entropy", 0.0, (double)d.N * d.V * sizeof(T) * 2);
         hipLaunchKernelGGL(ce_fwd_kernel<T>, dim3((d.N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0,
-                           st->stream, (T*)(S + sl.dlogits), aux, row_loss, d.N, d.V, d.Vld);
+                           st->launch, (T*)(S + sl.dlogits), aux, row_loss, d.N, d.V, d.Vld);
         TRY(after_launch());
-        hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(256), 0, st->stream, row_loss, (float*)out, d.N);
+        hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(256), 0, st->launch, row_loss, (float*)out, d.N);
         TRY(after_launch());
     }
     return AMDP_OK;
 }
+
+// While a Leaf is alive, launches go to the side stream, ordered after
+// everything enqueued on the main stream so far.
+struct Leaf {
+    amdp_stage* st;
+    bool ok = true;
+    explicit Leaf(amdp_stage* s) : st(s) {
+        if (!st->overlap) return;
+        hipEvent_t ev = st->next_event();
+        ok = hip_ok(hipEventRecord(ev, st->stream), "hipEventRecord(fork)") &&
+             hip_ok(hipStreamWaitEvent(st->side, ev, 0), "hipStreamWaitEvent(fork)");
+        if (ok) st->launch = st->side;
+    }
+    ~Leaf() { st->launch = st->stream; }
+};
+// The main stream waits for every leaf enqueued so far.
+int join_leaves(amdp_stage* st) {
+    if (!st->overlap) return AMDP_OK;
+    hipEvent_t ev = st->next_event();
+    HIP_TRY(hipEventRecord(ev, st->side));
+    HIP_TRY(hipStreamWaitEvent(st->stream, ev, 0));
+    return AMDP_OK;
+}
+#define LEAF(stmts) do { Leaf leaf_(st); if (!leaf_.ok) return AMDP_E_HIP; stmts } while (0)
 
 template <class T>
 int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, const void* dY, void* dX) {
@@ -551,98 +595,94 @@ int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, co
     const T* W = (const T*)st->version_ptr(vslot);
     char* S = st->act_ptr(aslot);
     float* g = st->at<float>(st->w.g);
-    void* buf[4] = {st->at<>(st->w.buf[0]), st->at<>(st->w.buf[1]), st->at<>(st->w.buf[2]),
-                    st->at<>(st->w.buf[3])};
-    void* dqkv = st->at<>(st->w.dqkv);
-    void* dffn = st->at<>(st->w.dffn);
-    void* dP = st->at<>(st->w.dP);
+    void* dO = st->at<>(st->w.dO);      // main chain only
+    void* dP = st->at<>(st->w.dP);      // main chain only
 
     const void* dcur = dY;
-    int cur_idx = -1;   // index of the buffer dcur lives in, -1 = caller's
     if (d.lm) {
         const SlotLayout& sl = st->w.slot;
-        {   // dE = dlogits^T z   (rows >= V are zero and land in the padding)
+        void* dz = st->at<>(st->w.lm_dz);
+        void* dyL = st->at<>(st->w.lm_dy);
+        LEAF({   // dE = dlogits^T z   (rows >= V are zero and land in the padding)
             GemmArgs a{};
             a.A = S + sl.dlogits; a.B = S + sl.z; a.C = g + d.off_embed();
             a.M = (int)d.Vld; a.N = d.D; a.K = d.N; a.ldc = d.D; a.epi.out_f32 = 1;
             TRY(gemm(st, G_TN, a, d.Vld, d.D));
-        }
+        });
         {   // dz = dlogits E
             GemmArgs a{};
-            a.A = S + sl.dlogits; a.B = W + d.off_embed(); a.C = buf[1];
+            a.A = S + sl.dlogits; a.B = W + d.off_embed(); a.C = dz;
             a.M = d.N; a.N = d.D; a.K = (int)d.Vld; a.ldc = d.D;
             TRY(gemm(st, G_NN, a, d.Vld, d.D));
         }
-        TRY((colreduce<T, true>(st, buf[1], S + sl.yL, (const float*)(S + sl.stf), g + d.off_lnf(), d.D)));
-        TRY(ln_bwd<T>(st, buf[1], S + sl.yL, (const float*)(S + sl.stf), W + d.off_lnf(), nullptr, buf[0]));
-        dcur = buf[0];
-        cur_idx = 0;
+        LEAF({ TRY((colreduce<T, true>(st, dz, S + sl.yL, (const float*)(S + sl.stf), g + d.off_lnf(), d.D))); });
+        TRY(ln_bwd<T>(st, dz, S + sl.yL, (const float*)(S + sl.stf), W + d.off_lnf(), nullptr, dyL));
+        dcur = dyL;
     }
 
     for (int l = d.L - 1; l >= 0; --l) {
         const LayerAct& a = st->w.slot.layers[l];
+        const Carve::BwdScratch& bw = st->w.bw[l];
         auto P = [&](int f) { return (const void*)(W + d.off(l, f)); };
         auto G = [&](int f) { return g + d.off(l, f); };
-        // three scratch buffers distinct from the one holding dcur
-        int free_idx[3], nf = 0;
-        for (int i = 0; i < 4 && nf < 3; ++i) if (i != cur_idx) free_idx[nf++] = i;
-        void* t1 = buf[free_idx[0]];
-        void* t2 = buf[free_idx[1]];
-        const int out_idx = free_idx[2];
-        void* dnext = (l == 0 && dX) ? dX : buf[out_idx];
+        void* ta = st->at<>(bw.t_a);
+        void* tb = st->at<>(bw.t_b);
+        void* tc = st->at<>(bw.t_c);
+        void* dffn = st->at<>(bw.dffn);
+        void* dqkv = st->at<>(bw.dqkv);
+        void* dnext = (l == 0 && dX) ? dX : st->at<>(bw.dxout);
         const float* st1 = (const float*)(S + a.st1);
         const float* st2 = (const float*)(S + a.st2);
 
         if (d.causal) {
             // y = y1 + MLP(LN2(y1))
-            TRY((colreduce<T, false>(st, dcur, nullptr, nullptr, G(B_2), d.D)));
-            TRY(linear_dw(st, S + a.h, dcur, G(W_2), d.N, d.D, d.F));
+            LEAF({ TRY((colreduce<T, false>(st, dcur, nullptr, nullptr, G(B_2), d.D)));
+                   TRY(linear_dw(st, S + a.h, dcur, G(W_2), d.N, d.D, d.F)); });
             TRY(linear_dx(st, dcur, P(W_2), S + a.u, nullptr, dffn, d.N, d.D, d.F));
-            TRY((colreduce<T, false>(st, dffn, nullptr, nullptr, G(B_1), d.F)));
-            TRY(linear_dw(st, S + a.c, dffn, G(W_1), d.N, d.F, d.D));
-            TRY(linear_dx(st, dffn, P(W_1), nullptr, nullptr, t1, d.N, d.F, d.D));
-            TRY((colreduce<T, true>(st, t1, S + a.y1, st2, G(LN2_G), d.D)));
-            TRY(ln_bwd<T>(st, t1, S + a.y1, st2, P(LN2_G), dcur, t2));               // t2 = dy1
+            LEAF({ TRY((colreduce<T, false>(st, dffn, nullptr, nullptr, G(B_1), d.F)));
+                   TRY(linear_dw(st, S + a.c, dffn, G(W_1), d.N, d.F, d.D)); });
+            TRY(linear_dx(st, dffn, P(W_1), nullptr, nullptr, ta, d.N, d.F, d.D));          // ta = dc
+            LEAF({ TRY((colreduce<T, true>(st, ta, S + a.y1, st2, G(LN2_G), d.D))); });
+            TRY(ln_bwd<T>(st, ta, S + a.y1, st2, P(LN2_G), dcur, tb));                      // tb = dy1
             // y1 = x + Attn(LN1(x))
-            TRY((colreduce<T, false>(st, t2, nullptr, nullptr, G(B_O), d.D)));
-            TRY(linear_dw(st, S + a.o, t2, G(W_O), d.N, d.D, d.D));
-            TRY(linear_dx(st, t2, P(W_O), nullptr, nullptr, t1, d.N, d.D, d.D));       // t1 = dO
-            TRY(attention_bwd<T>(st, t1, S + a.qkv, S + a.P, dP, dqkv, valid));
-            TRY((colreduce<T, false>(st, dqkv, nullptr, nullptr, G(B_QKV), 3 * d.D)));
-            TRY(linear_dw(st, S + a.a, dqkv, G(W_QKV), d.N, 3 * d.D, d.D));
-            TRY(linear_dx(st, dqkv, P(W_QKV), nullptr, nullptr, t1, d.N, 3 * d.D, d.D));   // t1 = da
-            TRY((colreduce<T, true>(st, t1, S + a.xin, st1, G(LN1_G), d.D)));
-            TRY(ln_bwd<T>(st, t1, S + a.xin, st1, P(LN1_G), t2, dnext));
+            LEAF({ TRY((colreduce<T, false>(st, tb, nullptr, nullptr, G(B_O), d.D)));
+                   TRY(linear_dw(st, S + a.o, tb, G(W_O), d.N, d.D, d.D)); });
+            TRY(linear_dx(st, tb, P(W_O), nullptr, nullptr, dO, d.N, d.D, d.D));
+            TRY(attention_bwd<T>(st, dO, S + a.qkv, S + a.P, dP, dqkv, valid));
+            LEAF({ TRY((colreduce<T, false>(st, dqkv, nullptr, nullptr, G(B_QKV), 3 * d.D)));
+                   TRY(linear_dw(st, S + a.a, dqkv, G(W_QKV), d.N, 3 * d.D, d.D)); });
+            TRY(linear_dx(st, dqkv, P(W_QKV), nullptr, nullptr, tc, d.N, 3 * d.D, d.D));     // tc = da
+            LEAF({ TRY((colreduce<T, true>(st, tc, S + a.xin, st1, G(LN1_G), d.D))); });
+            TRY(ln_bwd<T>(st, tc, S + a.xin, st1, P(LN1_G), tb, dnext));
         } else {
             // y = LN2(r2), r2 = y1 + MLP(y1); y1 = LN1(r1), r1 = x + Attn(x)
-            TRY((colreduce<T, true>(st, dcur, S + a.c, st2, G(LN2_G), d.D)));
-            TRY(ln_bwd<T>(st, dcur, S + a.c, st2, P(LN2_G), nullptr, t2));            // t2 = dr2
-            TRY((colreduce<T, false>(st, t2, nullptr, nullptr, G(B_2), d.D)));
-            TRY(linear_dw(st, S + a.h, t2, G(W_2), d.N, d.D, d.F));
-            TRY(linear_dx(st, t2, P(W_2), S + a.u, nullptr, dffn, d.N, d.D, d.F));
-            TRY((colreduce<T, false>(st, dffn, nullptr, nullptr, G(B_1), d.F)));
-            TRY(linear_dw(st, S + a.y1, dffn, G(W_1), d.N, d.F, d.D));
-            TRY(linear_dx(st, dffn, P(W_1), nullptr, t2, t1, d.N, d.F, d.D));         // t1 = dy1
-            TRY((colreduce<T, true>(st, t1, S + a.a, st1, G(LN1_G), d.D)));
-            TRY(ln_bwd<T>(st, t1, S + a.a, st1, P(LN1_G), nullptr, t2));             // t2 = dr1
-            TRY((colreduce<T, false>(st, t2, nullptr, nullptr, G(B_O), d.D)));
-            TRY(linear_dw(st, S + a.o, t2, G(W_O), d.N, d.D, d.D));
-            TRY(linear_dx(st, t2, P(W_O), nullptr, nullptr, t1, d.N, d.D, d.D));       // t1 = dO
-            TRY(attention_bwd<T>(st, t1, S + a.qkv, S + a.P, dP, dqkv, valid));
-            TRY((colreduce<T, false>(st, dqkv, nullptr, nullptr, G(B_QKV), 3 * d.D)));
-            TRY(linear_dw(st, S + a.xin, dqkv, G(W_QKV), d.N, 3 * d.D, d.D));
-            TRY(linear_dx(st, dqkv, P(W_QKV), nullptr, t2, dnext, d.N, 3 * d.D, d.D));
+            LEAF({ TRY((colreduce<T, true>(st, dcur, S + a.c, st2, G(LN2_G), d.D))); });
+            TRY(ln_bwd<T>(st, dcur, S + a.c, st2, P(LN2_G), nullptr, ta));                   // ta = dr2
+            LEAF({ TRY((colreduce<T, false>(st, ta, nullptr, nullptr, G(B_2), d.D)));
+                   TRY(linear_dw(st, S + a.h, ta, G(W_2), d.N, d.D, d.F)); });
+            TRY(linear_dx(st, ta, P(W_2), S + a.u, nullptr, dffn, d.N, d.D, d.F));
+            LEAF({ TRY((colreduce<T, false>(st, dffn, nullptr, nullptr, G(B_1), d.F)));
+                   TRY(linear_dw(st, S + a.y1, dffn, G(W_1), d.N, d.F, d.D)); });
+            TRY(linear_dx(st, dffn, P(W_1), nullptr, ta, tb, d.N, d.F, d.D));               // tb = dy1
+            LEAF({ TRY((colreduce<T, true>(st, tb, S + a.a, st1, G(LN1_G), d.D))); });
+            TRY(ln_bwd<T>(st, tb, S + a.a, st1, P(LN1_G), nullptr, tc));                    // tc = dr1
+            LEAF({ TRY((colreduce<T, false>(st, tc, nullptr, nullptr, G(B_O), d.D)));
+                   TRY(linear_dw(st, S + a.o, tc, G(W_O), d.N, d.D, d.D)); });
+            TRY(linear_dx(st, tc, P(W_O), nullptr, nullptr, dO, d.N, d.D, d.D));
+            TRY(attention_bwd<T>(st, dO, S + a.qkv, S + a.P, dP, dqkv, valid));
+            LEAF({ TRY((colreduce<T, false>(st, dqkv, nullptr, nullptr, G(B_QKV), 3 * d.D)));
+                   TRY(linear_dw(st, S + a.xin, dqkv, G(W_QKV), d.N, 3 * d.D, d.D)); });
+            TRY(linear_dx(st, dqkv, P(W_QKV), nullptr, tc, dnext, d.N, 3 * d.D, d.D));
         }
         dcur = dnext;
-        cur_idx = (l == 0 && dX) ? -1 : out_idx;
     }
-    return AMDP_OK;
+    return join_leaves(st);
 }
 
 template <class T>
 int publish(amdp_stage* st, int vslot) {
     const long n4 = st->d.n_alloc() / 4;
-    hipLaunchKernelGGL(publish_kernel<T>, dim3(stream_grid(n4)), dim3(STREAM_BLOCK), 0, st->stream,
+    hipLaunchKernelGGL(publish_kernel<T>, dim3(stream_grid(n4)), dim3(STREAM_BLOCK), 0, st->launch,
                        st->at<float>(st->w.theta), (T*)st->version_ptr(vslot), n4);
     return after_launch();
 }
@@ -710,12 +750,20 @@ extern "C" int amdp_stage_create(const amdp_stage_config_t* cfg, void* workspace
     if (workspace_bytes < st->w.total) { delete st; return AMDP_E_INVAL; }
     st->base = (char*)workspace;
     st->stream = (hipStream_t)hip_stream;
+    st->launch = st->stream;
     st->n_vslots = cfg->stash_slots + 1;
+    if (const char* e = getenv("AMDP_OVERLAP")) st->overlap = atoi(e) != 0;
+    if (st->overlap) {
+        bool ok = hip_ok(hipStreamCreateWithFlags(&st->side, hipStreamNonBlocking), "hipStreamCreateWithFlags");
+        for (int i = 0; ok && i < 16; ++i)
+            ok = hip_ok(hipEventCreateWithFlags(&st->events[i], hipEventDisableTiming), "hipEventCreateWithFlags");
+        if (!ok) { amdp_stage_destroy(st); return AMDP_E_HIP; }
+    }
     if (const char* e = getenv("AMDP_GEMM_TR")) st->use_tr = atoi(e) != 0;
     if (const char* e = getenv("AMDP_GEMM_TILE")) st->force_tile = atoi(e);
     // parameter buffers, version slots and the padding behind them start at zero
-    if (device_zero(st->stream, st->base, st->w.act) != AMDP_OK) {
-        delete st;
+    if (device_zero(st->launch, st->base, st->w.act) != AMDP_OK) {
+        amdp_stage_destroy(st);
         return AMDP_E_HIP;
     }
     *out = st;
@@ -724,6 +772,11 @@ extern "C" int amdp_stage_create(const amdp_stage_config_t* cfg, void* workspace
 
 extern "C" int amdp_stage_destroy(amdp_stage_t* st) {
     if (!st) return AMDP_E_INVAL;
+    if (st->side) {
+        hipStreamSynchronize(st->side);     // leaves still running read the workspace
+        hipStreamDestroy(st->side);
+    }
+    for (hipEvent_t e : st->events) if (e) hipEventDestroy(e);
     delete st;
     return AMDP_OK;
 }
@@ -733,14 +786,14 @@ extern "C" int amdp_stage_set_state(amdp_stage_t* st, const float* theta, const 
     if (!st || !theta) return AMDP_E_INVAL;
     const size_t nb = (size_t)st->d.n_params() * 4, na = (size_t)st->d.n_alloc() * 4;
     if ((uintptr_t)theta % 4 || (uintptr_t)m % 4 || (uintptr_t)v % 4) return AMDP_E_INVAL;
-    TRY(device_zero(st->stream, st->base + st->w.theta, na));
-    TRY(device_zero(st->stream, st->base + st->w.m, na));
-    TRY(device_zero(st->stream, st->base + st->w.v, na));
-    TRY(device_zero(st->stream, st->base + st->w.G, na));
-    TRY(device_zero(st->stream, st->base + st->w.g, na));
-    TRY(device_copy(st->stream, st->base + st->w.theta, theta, nb));
-    if (m) TRY(device_copy(st->stream, st->base + st->w.m, m, nb));
-    if (v) TRY(device_copy(st->stream, st->base + st->w.v, v, nb));
+    TRY(device_zero(st->launch, st->base + st->w.theta, na));
+    TRY(device_zero(st->launch, st->base + st->w.m, na));
+    TRY(device_zero(st->launch, st->base + st->w.v, na));
+    TRY(device_zero(st->launch, st->base + st->w.G, na));
+    TRY(device_zero(st->launch, st->base + st->w.g, na));
+    TRY(device_copy(st->launch, st->base + st->w.theta, theta, nb));
+    if (m) TRY(device_copy(st->launch, st->base + st->w.m, m, nb));
+    if (v) TRY(device_copy(st->launch, st->base + st->w.v, v, nb));
     for (int i = 0; i < MAX_VSLOTS; ++i) st->vs[i] = VSlot();
     for (int i = 0; i < MAX_ASLOTS; ++i) st->as[i] = ASlot();
     st->staged_slot = -1;
@@ -757,10 +810,10 @@ extern "C" int amdp_stage_get_state(amdp_stage_t* st, float* theta, float* m, fl
     if (!st) return AMDP_E_INVAL;
     const size_t nb = (size_t)st->d.n_params() * 4;
     if (((uintptr_t)theta | (uintptr_t)m | (uintptr_t)v | (uintptr_t)G) % 4) return AMDP_E_INVAL;
-    if (theta) TRY(device_copy(st->stream, theta, st->base + st->w.theta, nb));
-    if (m) TRY(device_copy(st->stream, m, st->base + st->w.m, nb));
-    if (v) TRY(device_copy(st->stream, v, st->base + st->w.v, nb));
-    if (G) TRY(device_copy(st->stream, G, st->base + st->w.G, nb));
+    if (theta) TRY(device_copy(st->launch, theta, st->base + st->w.theta, nb));
+    if (m) TRY(device_copy(st->launch, m, st->base + st->w.m, nb));
+    if (v) TRY(device_copy(st->launch, v, st->base + st->w.v, nb));
+    if (G) TRY(device_copy(st->launch, G, st->base + st->w.G, nb));
     if (step) *step = st->step;
     if (version) *version = st->cur_version;
     return AMDP_OK;
@@ -770,7 +823,7 @@ extern "C" int amdp_stage_get_staged_grad(amdp_stage_t* st, float* g) {
     if (!st || !g) return AMDP_E_INVAL;
     if (st->staged_slot < 0) return AMDP_E_MB_STATE;
     if ((uintptr_t)g % 4) return AMDP_E_INVAL;
-    return device_copy(st->stream, g, st->base + st->w.g, (size_t)st->d.n_params() * 4);
+    return device_copy(st->launch, g, st->base + st->w.g, (size_t)st->d.n_params() * 4);
 }
 
 extern "C" int amdp_stage_resident_versions(amdp_stage_t* st, uint32_t* versions, int32_t cap, int32_t* n) {
@@ -833,7 +886,7 @@ extern "C" int amdp_grad_accumulate(amdp_stage_t* st, int32_t mb) {
     if (aslot < 0 || !st->as[aslot].backwarded || st->staged_slot != aslot) return AMDP_E_MB_STATE;
     const long n4 = st->d.n_alloc() / 4;
     ProfScope ps(st, "grad_accumulate", 0.0, 12.0 * (double)st->d.n_params());
-    hipLaunchKernelGGL(accumulate_kernel, dim3(stream_grid(n4)), dim3(STREAM_BLOCK), 0, st->stream,
+    hipLaunchKernelGGL(accumulate_kernel, dim3(direct_grid(n4, ACC_BLOCK)), dim3(ACC_BLOCK), 0, st->launch,
                        st->at<float>(st->w.G), st->at<float>(st->w.g), n4);
     TRY(after_launch());
     st->as[aslot] = ASlot();
@@ -866,10 +919,10 @@ extern "C" int amdp_apply_update(amdp_stage_t* st, const amdp_adam_t* hp, uint32
     // read theta, m, v, G; write theta, m, v, the new version, and G = 0
     ProfScope ps(st, "adam_update", 0.0, (32.0 + (double)st->d.esz) * (double)st->d.n_params());
     if (st->d.bf)
-        hipLaunchKernelGGL(adam_kernel<bf16>, dim3(stream_grid(n4)), dim3(STREAM_BLOCK), 0, st->stream, th, m,
+        hipLaunchKernelGGL(adam_kernel<bf16>, dim3(direct_grid(n4, STREAM_BLOCK)), dim3(STREAM_BLOCK), 0, st->launch, th, m,
                            v, G, (bf16*)st->version_ptr(slot), n4, sc);
     else
-        hipLaunchKernelGGL(adam_kernel<float>, dim3(stream_grid(n4)), dim3(STREAM_BLOCK), 0, st->stream, th,
+        hipLaunchKernelGGL(adam_kernel<float>, dim3(direct_grid(n4, STREAM_BLOCK)), dim3(STREAM_BLOCK), 0, st->launch, th,
                            m, v, G, (float*)st->version_ptr(slot), n4, sc);
     TRY(after_launch());
     st->step = t;

@@ -13,25 +13,23 @@ constexpr int STREAM_BLOCK = 256;
 // Flat buffers are allocated in multiples of 1024 floats, so every kernel
 // here works on whole float4 quads: n4 = number of quads.
 
+// Launch shape of the streaming kernels: ONE 16-byte vector per lane and as
+// many small workgroups as that takes. Measured on MI355X over 3.2 GB buffers,
+// this beats every grid-stride variant (2048 resident workgroups looping: 4.6
+// TB/s for G += g; one vector per lane: 6.1-6.3 TB/s): the dispatcher walks
+// memory strictly in address order and each workgroup retires after one
+// round trip, which keeps the HBM channels evenly loaded.
+constexpr int ACC_BLOCK = 64;
+
 // G += g      (12 bytes of traffic per parameter)
-__global__ __launch_bounds__(STREAM_BLOCK) void accumulate_kernel(float* __restrict__ G,
-                                                                  const float* __restrict__ g, long n4) {
-    const long stride = (long)gridDim.x * STREAM_BLOCK;
-    long i = (long)blockIdx.x * STREAM_BLOCK + threadIdx.x;
+__global__ __launch_bounds__(ACC_BLOCK) void accumulate_kernel(float* __restrict__ G,
+                                                               const float* __restrict__ g, long n4) {
+    const long i = (long)blockIdx.x * ACC_BLOCK + threadIdx.x;
+    if (i >= n4) return;
     f32x4* G4 = (f32x4*)G;
-    const f32x4* g4 = (const f32x4*)g;
-    for (; i + 3 * stride < n4; i += 4 * stride) {
-        f32x4 a0 = G4[i], a1 = G4[i + stride], a2 = G4[i + 2 * stride], a3 = G4[i + 3 * stride];
-        f32x4 b0 = __builtin_nontemporal_load(&g4[i]);
-        f32x4 b1 = __builtin_nontemporal_load(&g4[i + stride]);
-        f32x4 b2 = __builtin_nontemporal_load(&g4[i + 2 * stride]);
-        f32x4 b3 = __builtin_nontemporal_load(&g4[i + 3 * stride]);
-        G4[i] = a0 + b0;
-        G4[i + stride] = a1 + b1;
-        G4[i + 2 * stride] = a2 + b2;
-        G4[i + 3 * stride] = a3 + b3;
-    }
-    for (; i < n4; i += stride) G4[i] = G4[i] + g4[i];
+    const f32x4 a = G4[i];
+    const f32x4 b = __builtin_nontemporal_load(&((const f32x4*)g)[i]);
+    G4[i] = a + b;
 }
 
 struct AdamScalars {
@@ -52,14 +50,14 @@ __global__ __launch_bounds__(STREAM_BLOCK) void adam_kernel(float* __restrict__ 
                                                             T* __restrict__ version_out, long n4,
                                                             AdamScalars hp) {
     typedef typename Pack4<T>::type out4;
-    const long stride = (long)gridDim.x * STREAM_BLOCK;
     f32x4* th4 = (f32x4*)theta;
     f32x4* m4 = (f32x4*)m;
     f32x4* v4 = (f32x4*)v;
     f32x4* G4 = (f32x4*)G;
     out4* o4 = (out4*)version_out;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-    for (long i = (long)blockIdx.x * STREAM_BLOCK + threadIdx.x; i < n4; i += stride) {
+    const long i = (long)blockIdx.x * STREAM_BLOCK + threadIdx.x;
+    if (i < n4) {
         f32x4 t = th4[i], mm = m4[i], vv = v4[i], gg = G4[i];
         out4 o;
 #pragma unroll
@@ -72,8 +70,11 @@ __global__ __launch_bounds__(STREAM_BLOCK) void adam_kernel(float* __restrict__ 
             mm[k] = mn; vv[k] = vn; t[k] = tn;
             o[k] = (T)tn;
         }
-        th4[i] = t; m4[i] = mm; v4[i] = vv; G4[i] = zero;
-        o4[i] = o;
+        __builtin_nontemporal_store(t, &th4[i]);
+        __builtin_nontemporal_store(mm, &m4[i]);
+        __builtin_nontemporal_store(vv, &v4[i]);
+        __builtin_nontemporal_store(zero, &G4[i]);
+        o4[i] = o;     // the new version is read again soon: keep it cacheable
     }
 }
 
@@ -119,10 +120,13 @@ __global__ __launch_bounds__(STREAM_BLOCK) void zero16_kernel(u32x4* __restrict_
     for (long i = (long)blockIdx.x * STREAM_BLOCK + threadIdx.x; i < n16; i += stride) dst[i] = z;
 }
 
+// grid for the grid-stride helpers (copy, zero, publish)
 inline int stream_grid(long n4) {
     long blocks = (n4 + STREAM_BLOCK - 1) / STREAM_BLOCK;
-    const long cap = 256 * 8;   // 256 CUs x 8 workgroups
+    const long cap = 256 * 64;
     return (int)(blocks < cap ? (blocks > 0 ? blocks : 1) : cap);
 }
+// grid for the one-vector-per-lane kernels
+inline unsigned direct_grid(long n4, int block) { return (unsigned)((n4 + block - 1) / block); }
 
 }  // namespace amdp
