@@ -246,6 +246,13 @@ typedef struct amdp_adam_t {
  * versions stay resident while an in-flight minibatch's forward has read them. */
 int amdp_apply_update(amdp_stage_t* stage, const amdp_adam_t* hp, uint32_t* new_version);
 
+/* Backward enqueues the parameter-gradient work (dW GEMMs, bias and LayerNorm
+ * column sums), which is off the dX critical path, on a side stream the stage
+ * owns and joins it back into the caller's stream before returning, so the
+ * caller still sees one stream. on = 0 keeps everything on the caller's stream
+ * (used to time kernels in isolation); default is on. */
+int amdp_stage_set_overlap(amdp_stage_t* stage, int32_t on);
+
 /* ------------------------------------------------------------------------
  * Measurement aid: per-kernel-class device time from HIP events recorded on
  * the stage's stream around every launch between begin and end. `flops` and

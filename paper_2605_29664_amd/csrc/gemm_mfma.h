@@ -15,6 +15,12 @@
 //
 // Shapes must be whole tiles: M % BM == 0, N % BN == 0, K % 64 == 0, 16-byte
 // aligned rows; anything else takes the generic kernel.
+//
+// Two main-loop pipelines, chosen by tile size from measurement: tiles up to
+// 128x128 (<= 188 VGPRs, two workgroups per compute unit) keep fragments live
+// across the barrier so the matrix cores work through it; the 256x256 tile
+// (one wave per SIMD, 256 accumulator registers) cannot afford those extra
+// live registers and uses the simpler load / compute / store / barrier order.
 #pragma once
 #include "common.h"
 
@@ -35,7 +41,7 @@ typedef __attribute__((address_space(3))) bf16 lds_bf16;
 typedef __attribute__((address_space(3))) float lds_f32;
 typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
 
-template <int R, bool KM>
+template <int R, bool KM, int NT = 256>
 struct OperandTile {
     // LDS rows are padded so that consecutive rows start 16 bytes (k-contiguous
     // tile: 128-bit reads of 16 rows) or 32 bytes (transposing reads: 4 rows x
@@ -44,9 +50,9 @@ struct OperandTile {
     static constexpr int ROWS = KM ? MF_BK : R;
     static constexpr int COLS = (KM ? R : MF_BK) + PAD;
     static constexpr int BYTES = ROWS * COLS * 2;
-    static constexpr int NV = R / 32;               // 16-byte vectors per thread per tile
+    static constexpr int NV = R * 8 / NT;           // 16-byte vectors per thread per tile
     static constexpr int VPR = KM ? R / 8 : 8;      // vectors per LDS row
-    static constexpr int ROWS_PER_PASS = 256 / VPR; // rows covered by the 256 threads in one pass
+    static constexpr int ROWS_PER_PASS = NT / VPR;  // rows covered by the NT threads in one pass
 
     // Byte offset, inside the operand, of the first vector this thread loads
     // (row stride rs and k stride ks in elements).
@@ -114,18 +120,19 @@ struct OperandTile {
     }
 };
 
-template <int BM, int BN, bool A_KM, bool B_KM, bool TR>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
-    constexpr int WM = BM / 2, WN = BN / 2;       // per-wave tile
+template <int BM, int BN, bool A_KM, bool B_KM, bool TR, int WGN = 2>
+__global__ __launch_bounds__(128 * WGN) void gemm_mfma_kernel(GemmArgs g) {
+    constexpr int NT = 128 * WGN;                 // waves are arranged 2 x WGN over the tile
+    constexpr int WM = BM / 2, WN = BN / WGN;     // per-wave tile
     constexpr int TM = WM / 32, TN = WN / 32;     // 32x32 MFMA tiles per wave
-    using TA = OperandTile<BM, A_KM>;
-    using TB = OperandTile<BN, B_KM>;
+    using TA = OperandTile<BM, A_KM, NT>;
+    using TB = OperandTile<BN, B_KM, NT>;
     constexpr int STAGE = TA::BYTES + TB::BYTES;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     lds_u8* lds = (lds_u8*)smem_raw;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
 
     // tile id -> (pm, pn): contiguous chunk of tiles per XCD (workgroups are
     // dealt round-robin to the 8 XCDs, each with its own L2), then groups of 8
@@ -174,6 +181,116 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 
     u32x4 ra[TA::NV], rb[TB::NV];
     const int nk = (k_hi - k_lo) / MF_BK;
+
+    constexpr int KSTEPS = MF_BK / 16;
+    static_assert(KSTEPS == 4, "the pipeline below is written for four k-steps per tile");
+    constexpr int NDS = TM * (A_KM && TR ? 2 : 1) + TN * (B_KM && TR ? 2 : 1);   // LDS reads per k-step
+    constexpr int NMF = TM * TN;                                                 // MFMAs per k-step
+    constexpr int NVM = TA::NV + TB::NV;                                         // global loads / LDS writes per tile
+
+  if constexpr (BM * BN <= 128 * 128 || WGN == 4) {
+    // Fragments are double buffered in registers: buffer kk&1 feeds k-step kk.
+    bf16x8 va[2][TM], vb[2][TN];
+    auto load_frags = [&](int buf, int stage, int kk) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) va[buf][i] = TA::template frag<TR>(fa + stage, i * 32, kk);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) vb[buf][j] = TB::template frag<TR>(fb + stage, j * 32, kk);
+    };
+    auto mfma_step = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[buf][i], vb[buf][j], acc[i][j], 0, 0, 0);
+    };
+    // scheduling directive: NMF MFMAs, each followed by one LDS read while any remain
+    auto interleave_reads = [&]() {
+#if AMDP_GEMM_SCHED
+#pragma unroll
+        for (int t = 0; t < NMF; ++t) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (t < NDS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        if (NDS > NMF) __builtin_amdgcn_sched_group_barrier(0x100, NDS - NMF, 0);
+#endif
+    };
+
+    // Pipeline. Tile kt is multiplied out of LDS stage kt&1 in four k-steps.
+    //   k-steps 0,1 : MFMAs, LDS reads of the next k-step's fragments
+    //   k-step 2    : MFMAs, LDS reads for k-step 3, LDS WRITES of tile kt+1 (its
+    //                 global loads were issued a whole tile earlier), then the
+    //                 global loads of tile kt+2 into the freed registers
+    //   barrier     : tile kt+1 complete in LDS; k-step 3's fragments are already
+    //                 in registers, so the matrix cores keep working across it
+    //   k-step 3    : MFMAs, LDS reads of tile kt+1's first fragments
+    if (nk > 0) {
+        TA::load(ra, pa, a_pass);
+        TB::load(rb, pb, b_pass);
+        TA::store(ra, sa);
+        TB::store(rb, sb);
+        if (nk > 1) {
+            pa += a_step;
+            pb += b_step;
+            TA::load(ra, pa, a_pass);
+            TB::load(rb, pb, b_pass);
+        }
+    }
+    __syncthreads();
+    if (nk > 0) load_frags(0, 0, 0);
+
+    int kt = 0;
+    for (; kt + 2 < nk; ++kt) {     // steady state: tiles kt+1 and kt+2 exist
+        const int cur = (kt & 1) * STAGE, nxt = STAGE - cur;
+        load_frags(1, cur, 1);
+        mfma_step(0);
+        interleave_reads();
+        load_frags(0, cur, 2);
+        mfma_step(1);
+        interleave_reads();
+        load_frags(1, cur, 3);
+        mfma_step(0);
+        TA::store(ra, sa + nxt);
+        TB::store(rb, sb + nxt);
+        pa += a_step;
+        pb += b_step;
+        TA::load(ra, pa, a_pass);
+        TB::load(rb, pb, b_pass);
+#if AMDP_GEMM_SCHED
+        __builtin_amdgcn_sched_group_barrier(0x100, NDS, 0);
+#pragma unroll
+        for (int t = 0; t < NMF; ++t) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (t < NVM) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        }
+        if (NVM > NMF) __builtin_amdgcn_sched_group_barrier(0x200, NVM - NMF, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, NVM, 0);
+#endif
+        __syncthreads();
+        load_frags(0, nxt, 0);
+        mfma_step(1);
+        interleave_reads();
+    }
+    for (; kt < nk; ++kt) {         // last two tiles: nothing left to load
+        const int cur = (kt & 1) * STAGE, nxt = STAGE - cur;
+        const bool more = kt + 1 < nk;
+        load_frags(1, cur, 1);
+        mfma_step(0);
+        load_frags(0, cur, 2);
+        mfma_step(1);
+        load_frags(1, cur, 3);
+        mfma_step(0);
+        if (more) {
+            TA::store(ra, sa + nxt);
+            TB::store(rb, sb + nxt);
+        }
+        __syncthreads();
+        if (more) load_frags(0, nxt, 0);
+        mfma_step(1);
+    }
+    __syncthreads();
+
+  } else {
     if (nk > 0) {
         TA::load(ra, pa, a_pass);
         TB::load(rb, pb, b_pass);
@@ -181,10 +298,6 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
         TB::store(rb, sb);
     }
     __syncthreads();
-
-    constexpr int KSTEPS = MF_BK / 16;
-    constexpr int NDS = TM * (A_KM && TR ? 2 : 1) + TN * (B_KM && TR ? 2 : 1);   // LDS reads per k-step
-    constexpr int NMF = TM * TN;                                                 // MFMAs per k-step
 
     // One k-tile of matrix work out of the LDS stage at byte offset `cur`.
     // Fragments are double buffered in registers: the LDS reads of k-step kk+1
@@ -259,6 +372,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
         __syncthreads();
     }
 
+  }
+
     // Epilogue through LDS: each wave parks one 32-row strip of its tile in LDS
     // as fp32, then reads it back row-wise so that every lane handles 8
     // consecutive columns and the wave writes whole row segments.
@@ -314,11 +429,11 @@ inline bool mfma_shape_ok(const GemmArgs& g, bool a_km, bool b_km) {
     return true;
 }
 
-template <int BM, int BN, bool A_KM, bool B_KM, bool TR>
+template <int BM, int BN, bool A_KM, bool B_KM, bool TR, int WGN = 2>
 inline hipError_t launch_gemm_mfma_inst(const GemmArgs& g, hipStream_t st) {
     constexpr size_t lds = mfma_lds_bytes<BM, BN, A_KM, B_KM>();
     static_assert(lds <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
-    auto kern = gemm_mfma_kernel<BM, BN, A_KM, B_KM, TR>;
+    auto kern = gemm_mfma_kernel<BM, BN, A_KM, B_KM, TR, WGN>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -326,7 +441,7 @@ inline hipError_t launch_gemm_mfma_inst(const GemmArgs& g, hipStream_t st) {
         attr_set = true;
     }
     dim3 grid((g.M / BM) * (g.N / BN), 1, g.batch);
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, g);
+    hipLaunchKernelGGL(kern, grid, dim3(128 * WGN), lds, st, g);
     return hipGetLastError();
 }
 

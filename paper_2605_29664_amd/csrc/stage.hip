@@ -310,8 +310,9 @@ int gemm_bf16_layout(amdp_stage* st, const GemmArgs& g) {
     ProfScope ps(st, name, gemm_flops(g), 0.0);
     switch (tile) {
         case 256:
-            e = tr ? launch_gemm_mfma_inst<256, 256, A_KM, B_KM, true>(g, st->launch)
-                   : launch_gemm_mfma_inst<256, 256, A_KM, B_KM, false>(g, st->launch);
+            // eight waves (two per SIMD), each 128x64 of the tile
+            e = tr ? launch_gemm_mfma_inst<256, 256, A_KM, B_KM, true, 4>(g, st->launch)
+                   : launch_gemm_mfma_inst<256, 256, A_KM, B_KM, false, 4>(g, st->launch);
             break;
         case 128:
             e = tr ? launch_gemm_mfma_inst<128, 128, A_KM, B_KM, true>(g, st->launch)
@@ -752,13 +753,14 @@ extern "C" int amdp_stage_create(const amdp_stage_config_t* cfg, void* workspace
     st->stream = (hipStream_t)hip_stream;
     st->launch = st->stream;
     st->n_vslots = cfg->stash_slots + 1;
-    if (const char* e = getenv("AMDP_OVERLAP")) st->overlap = atoi(e) != 0;
-    if (st->overlap) {
+    const char* ov = getenv("AMDP_OVERLAP");
+    {
         bool ok = hip_ok(hipStreamCreateWithFlags(&st->side, hipStreamNonBlocking), "hipStreamCreateWithFlags");
         for (int i = 0; ok && i < 16; ++i)
             ok = hip_ok(hipEventCreateWithFlags(&st->events[i], hipEventDisableTiming), "hipEventCreateWithFlags");
         if (!ok) { amdp_stage_destroy(st); return AMDP_E_HIP; }
     }
+    if (ov) st->overlap = atoi(ov) != 0;
     if (const char* e = getenv("AMDP_GEMM_TR")) st->use_tr = atoi(e) != 0;
     if (const char* e = getenv("AMDP_GEMM_TILE")) st->force_tile = atoi(e);
     // parameter buffers, version slots and the padding behind them start at zero
@@ -972,3 +974,10 @@ extern "C" int amdp_stage_profile_end(amdp_stage_t* st, amdp_profile_entry_t* ou
 }
 
 extern "C" const char* amdp_last_hip_error(void) { return g_hip_detail; }
+
+extern "C" int amdp_stage_set_overlap(amdp_stage_t* st, int32_t on) {
+    if (!st) return AMDP_E_INVAL;
+    if (on && !st->side) return AMDP_E_INVAL;   // the stage was created without a side stream
+    st->overlap = on != 0;
+    return AMDP_OK;
+}
