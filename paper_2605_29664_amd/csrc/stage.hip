@@ -4,6 +4,7 @@
 // minibatches, and the order of kernel launches for forward, backward,
 // accumulate and update. Everything is enqueued on one HIP stream.
 #include "amdp.h"
+#include "attention.h"
 #include "common.h"
 #include "gemm_mfma.h"
 #include "gemm_simple.h"
@@ -95,11 +96,12 @@ bool make_dims(const amdp_stage_config_t* c, Dims* d) {
 
 // ---- workspace carving ------------------------------------------------------
 struct LayerAct {   // byte offsets inside an activation slot
-    size_t xin, a, qkv, P, o, y1, c, u, h, st1, st2;
+    size_t xin, a, qkv, P, o, y1, c, u, h, st1, st2;   // P: probabilities, or the fused kernels' log-sum-exp
 };
 struct SlotLayout {
     std::vector<LayerAct> layers;
     size_t yL = 0, z = 0, stf = 0, dlogits = 0;
+    size_t valid = 0;   // copy of the padding mask (valid_len[b]) for backward
     size_t bytes = 0;
 };
 struct Carve {
@@ -113,6 +115,16 @@ struct Carve {
     SlotLayout slot;
 };
 
+// Fused attention is used whenever the shape allows it (AMDP_FLASH=0 in the
+// environment switches it off for comparison runs). With it, only the fp32
+// log-sum-exp per (sequence, head, query) is kept instead of the s x s
+// probabilities.
+inline int flash_mode() {
+    const char* e = getenv("AMDP_FLASH");
+    return e ? atoi(e) : 1;
+}
+inline bool flash_shape_ok(const Dims& d) { return d.bf && (d.dh == 64 || d.dh == 128) && d.s % 128 == 0; }
+
 void carve(const Dims& d, const amdp_stage_config_t& c, Carve* w) {
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = round_up(off + bytes, ALIGN); return o; };
@@ -123,7 +135,8 @@ void carve(const Dims& d, const amdp_stage_config_t& c, Carve* w) {
     w->versions = take(w->version_bytes * (size_t)(c.stash_slots + 1));
 
     const size_t ND = (size_t)d.N * d.D * d.esz, NF = (size_t)d.N * d.F * d.esz;
-    const size_t PP = (size_t)d.b * d.H * d.s * d.s * d.esz;
+    const bool fused = flash_mode() == 1 && flash_shape_ok(d);
+    const size_t PP = fused ? (size_t)d.b * d.H * d.s * 4 : (size_t)d.b * d.H * d.s * d.s * d.esz;
     {
         size_t so = 0;
         auto st = [&](size_t bytes) { size_t o = so; so = round_up(so + bytes, ALIGN); return o; };
@@ -138,6 +151,7 @@ void carve(const Dims& d, const amdp_stage_config_t& c, Carve* w) {
             w->slot.yL = st(ND); w->slot.z = st(ND); w->slot.stf = st((size_t)d.N * 8);
             w->slot.dlogits = st((size_t)d.N * d.Vld * d.esz);
         }
+        w->slot.valid = st((size_t)d.b * 4);
         w->slot.bytes = so;
     }
     w->slot_bytes = w->slot.bytes;
@@ -202,6 +216,7 @@ struct amdp_stage {
     hipEvent_t events[16] = {};
     int ev_next = 0;
     bool overlap = true;
+    int flash = 1;          // fused attention: 1 on (default), 0 off, 2 test mode: run after the three-kernel path
     hipEvent_t next_event() { ev_next = (ev_next + 1) % 16; return events[ev_next]; }
 
     template <class P = void> P* at(size_t off) const { return (P*)(base + off); }
@@ -398,9 +413,60 @@ GemmArgs attn_batch(const Dims& d) {
     return g;
 }
 
+inline bool flash_ok(const Dims& d) { return flash_shape_ok(d); }
+
+int flash_fwd(amdp_stage* st, const void* qkv, void* o, float* lse2, const int32_t* valid) {
+    const Dims& d = st->d;
+    const float sc = LOG2E / sqrtf((float)d.dh);
+    dim3 grid(d.s / 128, d.b * d.H);
+    ProfScope ps(st, "flash_attention_fwd", 4.0 * d.b * d.H * (double)d.s * d.s * d.dh * (d.causal ? (d.s + 1.0) / (2.0 * d.s) : 1.0), 0.0);
+#define FLASH_FWD(DH, C) hipLaunchKernelGGL((flash_fwd_kernel<DH, C>), grid, dim3(256), 0, st->launch, (const bf16*)qkv, \
+                                            (bf16*)o, lse2, valid, d.s, d.H, d.D, sc)
+    if (d.dh == 128) { if (d.causal) FLASH_FWD(128, true); else FLASH_FWD(128, false); }
+    else { if (d.causal) FLASH_FWD(64, true); else FLASH_FWD(64, false); }
+#undef FLASH_FWD
+    return after_launch();
+}
+
+// delta, dK/dV and dQ kernels; lse2 is what flash_fwd saved, delta is scratch [b*H*s] fp32
+int flash_bwd(amdp_stage* st, const void* dO, const void* qkv, const void* o, const float* lse2, float* delta,
+              void* dqkv, const int32_t* valid) {
+    const Dims& d = st->d;
+    const float scale = 1.0f / sqrtf((float)d.dh);
+    const double unit = 2.0 * d.b * d.H * (double)d.s * d.s * d.dh * (d.causal ? (d.s + 1.0) / (2.0 * d.s) : 1.0);
+    dim3 grid(d.s / 128, d.b * d.H);
+    {
+        ProfScope ps(st, "attention_delta", 0.0, 2.0 * d.N * d.D * 2.0);
+        if (d.dh == 128)
+            hipLaunchKernelGGL(attn_delta_kernel<128>, dim3((d.N + 3) / 4), dim3(256), 0, st->launch, (const bf16*)dO,
+                               (const bf16*)o, delta, d.N, d.s, d.H, d.D);
+        else
+            hipLaunchKernelGGL(attn_delta_kernel<64>, dim3((d.N + 3) / 4), dim3(256), 0, st->launch, (const bf16*)dO,
+                               (const bf16*)o, delta, d.N, d.s, d.H, d.D);
+        TRY(after_launch());
+    }
+#define FLASH_BWD(KERN, DH, C) hipLaunchKernelGGL((KERN<DH, C>), grid, dim3(256), 0, st->launch, (const bf16*)qkv, \
+                                                  (const bf16*)dO, lse2, (const float*)delta, (bf16*)dqkv, valid, d.s, d.H, d.D, scale)
+    {
+        ProfScope ps(st, "flash_attention_bwd_dkdv", 4.0 * unit, 0.0);   // S, dP, dV, dK
+        if (d.dh == 128) { if (d.causal) FLASH_BWD(flash_bwd_dkv_kernel, 128, true); else FLASH_BWD(flash_bwd_dkv_kernel, 128, false); }
+        else { if (d.causal) FLASH_BWD(flash_bwd_dkv_kernel, 64, true); else FLASH_BWD(flash_bwd_dkv_kernel, 64, false); }
+        TRY(after_launch());
+    }
+    {
+        ProfScope ps(st, "flash_attention_bwd_dq", 1.0 * unit, 0.0);     // dQ (S and dP are recomputed, not counted)
+        if (d.dh == 128) { if (d.causal) FLASH_BWD(flash_bwd_dq_kernel, 128, true); else FLASH_BWD(flash_bwd_dq_kernel, 128, false); }
+        else { if (d.causal) FLASH_BWD(flash_bwd_dq_kernel, 64, true); else FLASH_BWD(flash_bwd_dq_kernel, 64, false); }
+        TRY(after_launch());
+    }
+#undef FLASH_BWD
+    return AMDP_OK;
+}
+
 template <class T>
 int attention_fwd(amdp_stage* st, const void* qkv_, void* P_, void* o_, const int32_t* valid) {
     const Dims& d = st->d;
+    if (st->flash == 1 && flash_ok(d)) return flash_fwd(st, qkv_, o_, (float*)P_, valid);
     const T* qkv = (const T*)qkv_;
     const long ld3 = 3L * d.D;
     {   // S = Q K^T
@@ -430,14 +496,18 @@ int attention_fwd(amdp_stage* st, const void* qkv_, void* P_, void* o_, const in
         g.causal = d.causal ? 2 : 0;
         TRY(gemm(st, G_NN, g, d.s, ld3));
     }
+    if (st->flash == 2 && flash_ok(d))   // test mode: overwrite O with the fused kernel's result
+        TRY(flash_fwd(st, qkv_, o_, st->at<float>(st->w.dP), valid));
     return AMDP_OK;
 }
 
 // dqkv from d_out, the saved qkv and probabilities; dP is scratch [b*H, s, s]
 template <class T>
-int attention_bwd(amdp_stage* st, const void* dO_, const void* qkv_, const void* P_, void* dP_,
+int attention_bwd(amdp_stage* st, const void* dO_, const void* qkv_, const void* P_, const void* o_, void* dP_,
                   void* dqkv_, const int32_t* valid) {
     const Dims& d = st->d;
+    if (st->flash == 1 && flash_ok(d))
+        return flash_bwd(st, dO_, qkv_, o_, (const float*)P_, (float*)dP_, dqkv_, valid);
     const T* qkv = (const T*)qkv_;
     T* dqkv = (T*)dqkv_;
     const long ld3 = 3L * d.D;
@@ -519,6 +589,7 @@ int forward_impl(amdp_stage* st, int aslot, int vslot, const void* X, const int3
     const size_t ND = (size_t)d.N * d.D * sizeof(T);
     // aux is the padding mask for bidirectional blocks, the targets on an LM-head stage
     const int32_t* valid = (!d.causal && !d.lm) ? aux : nullptr;
+    if (valid) TRY(device_copy(st->launch, S + st->w.slot.valid, valid, (size_t)d.b * 4));
     {
         ProfScope ps(st, "copy_input", 0.0, 2.0 * (double)ND);
         TRY(device_copy(st->launch, S + st->w.slot.layers[0].xin, X, ND));
@@ -649,7 +720,7 @@ int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, co
             LEAF({ TRY((colreduce<T, false>(st, tb, nullptr, nullptr, G(B_O), d.D)));
                    TRY(linear_dw(st, S + a.o, tb, G(W_O), d.N, d.D, d.D)); });
             TRY(linear_dx(st, tb, P(W_O), nullptr, nullptr, dO, d.N, d.D, d.D));
-            TRY(attention_bwd<T>(st, dO, S + a.qkv, S + a.P, dP, dqkv, valid));
+            TRY(attention_bwd<T>(st, dO, S + a.qkv, S + a.P, S + a.o, dP, dqkv, valid));
             LEAF({ TRY((colreduce<T, false>(st, dqkv, nullptr, nullptr, G(B_QKV), 3 * d.D)));
                    TRY(linear_dw(st, S + a.a, dqkv, G(W_QKV), d.N, 3 * d.D, d.D)); });
             TRY(linear_dx(st, dqkv, P(W_QKV), nullptr, nullptr, tc, d.N, 3 * d.D, d.D));     // tc = da
@@ -670,7 +741,7 @@ int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, co
             LEAF({ TRY((colreduce<T, false>(st, tc, nullptr, nullptr, G(B_O), d.D)));
                    TRY(linear_dw(st, S + a.o, tc, G(W_O), d.N, d.D, d.D)); });
             TRY(linear_dx(st, tc, P(W_O), nullptr, nullptr, dO, d.N, d.D, d.D));
-            TRY(attention_bwd<T>(st, dO, S + a.qkv, S + a.P, dP, dqkv, valid));
+            TRY(attention_bwd<T>(st, dO, S + a.qkv, S + a.P, S + a.o, dP, dqkv, valid));
             LEAF({ TRY((colreduce<T, false>(st, dqkv, nullptr, nullptr, G(B_QKV), 3 * d.D)));
                    TRY(linear_dw(st, S + a.xin, dqkv, G(W_QKV), d.N, 3 * d.D, d.D)); });
             TRY(linear_dx(st, dqkv, P(W_QKV), nullptr, tc, dnext, d.N, 3 * d.D, d.D));
@@ -761,6 +832,7 @@ extern "C" int amdp_stage_create(const amdp_stage_config_t* cfg, void* workspace
         if (!ok) { amdp_stage_destroy(st); return AMDP_E_HIP; }
     }
     if (ov) st->overlap = atoi(ov) != 0;
+    st->flash = flash_mode();
     if (const char* e = getenv("AMDP_GEMM_TR")) st->use_tr = atoi(e) != 0;
     if (const char* e = getenv("AMDP_GEMM_TILE")) st->force_tile = atoi(e);
     // parameter buffers, version slots and the padding behind them start at zero
@@ -869,10 +941,11 @@ extern "C" int amdp_stage_backward(amdp_stage_t* st, int32_t mb, uint32_t versio
     if (st->staged_slot >= 0) return AMDP_E_MB_STATE;
     const int vslot = st->find_version(version);
     if (vslot < 0) return AMDP_E_VERSION;
-    // Masked keys carry probability exactly 0, so the padding mask is not needed
-    // again: dS = P * (...) vanishes there by itself.
-    int rc = d.bf ? backward_impl<bf16>(st, aslot, vslot, nullptr, dY, dX)
-                  : backward_impl<float>(st, aslot, vslot, nullptr, dY, dX);
+    // the padding mask was saved with the activations (the fused attention
+    // backward recomputes the probabilities and needs it again)
+    const int32_t* valid = (!d.causal && !d.lm) ? (const int32_t*)(st->act_ptr(aslot) + st->w.slot.valid) : nullptr;
+    int rc = d.bf ? backward_impl<bf16>(st, aslot, vslot, valid, dY, dX)
+                  : backward_impl<float>(st, aslot, vslot, valid, dY, dX);
     if (rc != AMDP_OK) return rc;
     ASlot& a = st->as[aslot];
     a.backwarded = true;

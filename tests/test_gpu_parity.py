@@ -22,7 +22,7 @@ def _report(name, rep):
 
 @pytest.fixture(autouse=True)
 def _clean_env():
-    saved = {k: os.environ.get(k) for k in ("AMDP_GEMM_TR", "AMDP_GEMM_TILE")}
+    saved = {k: os.environ.get(k) for k in ("AMDP_GEMM_TR", "AMDP_GEMM_TILE", "AMDP_FLASH")}
     yield
     for k, v in saved.items():
         if v is None:
@@ -67,6 +67,13 @@ def test_tile_bf16_mfma(key, tr):
     os.environ["AMDP_GEMM_TR"] = tr
     rep = run_parity(W.TINY[key], n_windows=1, verbose=False)
     _report(f"{key}_tr{tr}", rep)
+    assert rep["ok"], worst_entries(rep)
+
+
+@pytest.mark.parametrize("key", ["gpt_tile128", "bert_tile128"])
+def test_tile_bf16_head_dim_128(key):
+    rep = run_parity(W.TINY[key], n_windows=1, verbose=False)
+    _report(key, rep)
     assert rep["ok"], worst_entries(rep)
 
 

@@ -101,6 +101,11 @@ TINY = {
                               depth=6, pipelines=3, stage=3, threshold=6),
     "bert_tile": StageWorkload("tile_bert", 18, BERT_POSTLN_BIDIR, 2, 256, 4, 1024, 256, 2, BF16,
                                depth=4, pipelines=2, stage=1, threshold=4),
+    # head dimension 128, two key blocks per query block
+    "gpt_tile128": StageWorkload("tile_gpt_dh128", 20, GPT_PRELN_CAUSAL, 1, 256, 2, 512, 256, 2, BF16,
+                                 depth=4, pipelines=2, stage=1, threshold=4),
+    "bert_tile128": StageWorkload("tile_bert_dh128", 21, BERT_POSTLN_BIDIR, 1, 256, 2, 512, 384, 2, BF16,
+                                  depth=4, pipelines=2, stage=1, threshold=4),
     "lmhead_tile": StageWorkload("tile_lmhead", 19, GPT_PRELN_CAUSAL, 1, 256, 4, 1024, 256, 2, BF16,
                                  has_lm_head=True, vocab=1931,
                                  depth=4, pipelines=2, stage=3, threshold=4),
