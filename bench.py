@@ -40,6 +40,19 @@ def algorithmic_flops_per_minibatch(w):
     return 3.0 * fwd
 
 
+def recorded_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload` from the committed
+    rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summaries under profiles/ (lines
+    `traffic: <workload> <kernel> <bytes>`), or None."""
+    import glob
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*hbm_traffic.md"))):
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 4 and parts[0] == "traffic:" and parts[1] == workload and parts[2] == kernel:
+                return float(parts[3])
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -155,7 +168,8 @@ def main():
             r = gemms[dom]
             ach = r["flops"] / r["ms"] / 1e9
             return {"kernel": dom, "bound": "mfma" if w.dtype == 1 else "alu", "achieved": ach, "peak": peak,
-                    "unit": "TFLOP/s", "frac": ach / peak, "traffic": None, "launches": r["launches"],
+                    "unit": "TFLOP/s", "frac": ach / peak, "traffic": recorded_traffic(w.name, dom),
+                    "launches": r["launches"],
                     "avg_launch_ms": r["ms"] / r["launches"], "flops_per_launch": r["flops"] / r["launches"]}
 
         # (a) as timed: gradient leaves overlap with the dX chain on the side stream
