@@ -138,36 +138,47 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
                 st[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_row<STRIDE>(tK, kt * 32, kk, lane), bq[kk],
                                                                 st[kt], 0, 0, 0);
         }
+        // Softmax in the log2 domain on the raw scores: x = c*s, p = exp2(c*s - m).
+        // Masks only where a block touches the diagonal or the padding edge
+        // (wave-uniform test); everything else is one max, one fma, one exp2 and
+        // one add per score.
+        const bool edge = (CAUSAL && k0 + BKV - 1 > q_wave) || k0 + BKV > klimit;
+        if (edge) {
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = k0 + kt * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                    if ((CAUSAL && key > q) || key >= klimit) st[kt][v] = -INFINITY;
+                }
+        }
         float mloc = -INFINITY;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int key = k0 + kt * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                float x = st[kt][v] * scale_log2e;
-                if ((CAUSAL && key > q) || key >= klimit) x = -INFINITY;
-                st[kt][v] = x;
-                mloc = fmaxf(mloc, x);
-            }
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+            for (int v = 0; v < 16; ++v) mloc = fmaxf(mloc, st[kt][v]);
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64)) * scale_log2e;      // scale > 0 commutes with max
         const float m_new = fmaxf(m_run, mloc);
         const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = exp2f(m_run - m_use);
         float lsum = 0.f;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const float p = exp2f(st[kt][v] - m_use);
+                const float p = exp2f(fmaf(st[kt][v], scale_log2e, -m_use));
                 st[kt][v] = p;
                 lsum += p;
             }
-        l_run = l_run * alpha + lsum;
-        m_run = m_new;
+        if (m_new != m_run) {          // most blocks leave the running maximum alone
+            const float alpha = exp2f(m_run - m_use);
+            l_run *= alpha;
 #pragma unroll
-        for (int t = 0; t < DT; ++t)
+            for (int t = 0; t < DT; ++t)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[t][v] *= alpha;
+                for (int v = 0; v < 16; ++v) acc[t][v] *= alpha;
+            m_run = m_new;
+        }
+        l_run += lsum;
         // O^T += V^T P^T
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
@@ -307,10 +318,10 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16* __restri
                 for (int e = 0; e < 4; ++e) {
                     const int v = 4 * gq + e;
                     const int q = q0 + qt * 32 + 8 * gq + 4 * half + e;
-                    float p = exp2f(sc[v] * sl2 - l4[e]);
+                    float p = exp2f(fmaf(sc[v], sl2, -l4[e]));
                     if ((CAUSAL && key > q) || key >= klimit) p = 0.f;
                     sc[v] = p;
-                    dp[v] = p * (dp[v] - d4[e]) * scale;
+                    dp[v] = (p * scale) * (dp[v] - d4[e]);
                 }
             }
 #pragma unroll
@@ -393,9 +404,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int key = k0 + kt * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                float p = exp2f(sc[v] * sl2 - lse_q);
+                float p = exp2f(fmaf(sc[v], sl2, -lse_q));
                 if ((CAUSAL && key > q) || key >= klimit) p = 0.f;
-                dp[v] = p * (dp[v] - delta_q) * scale;
+                dp[v] = (p * scale) * (dp[v] - delta_q);
             }
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
