@@ -44,9 +44,12 @@ typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
 template <int R, bool KM, int NT = 256>
 struct OperandTile {
     // LDS rows are padded so that consecutive rows start 16 bytes (k-contiguous
-    // tile: 128-bit reads of 16 rows) or 32 bytes (transposing reads: 4 rows x
-    // 32 bytes per 16-lane group) further round the banks.
-    static constexpr int PAD = KM ? 16 : 8;
+    // tile: 128-bit reads of 16 rows) or 64 bytes (transposing reads: half a
+    // wave reads 4 rows x 64 bytes at a time) further round the 64 banks.
+#ifndef AMDP_KM_PAD
+#define AMDP_KM_PAD 32
+#endif
+    static constexpr int PAD = KM ? AMDP_KM_PAD : 8;
     static constexpr int ROWS = KM ? MF_BK : R;
     static constexpr int COLS = (KM ? R : MF_BK) + PAD;
     static constexpr int BYTES = ROWS * COLS * 2;

@@ -860,6 +860,7 @@ extern "C" int amdp_stage_set_state(amdp_stage_t* st, const float* theta, const 
     if (!st || !theta) return AMDP_E_INVAL;
     const size_t nb = (size_t)st->d.n_params() * 4, na = (size_t)st->d.n_alloc() * 4;
     if ((uintptr_t)theta % 4 || (uintptr_t)m % 4 || (uintptr_t)v % 4) return AMDP_E_INVAL;
+    TRY(join_leaves(st));
     TRY(device_zero(st->launch, st->base + st->w.theta, na));
     TRY(device_zero(st->launch, st->base + st->w.m, na));
     TRY(device_zero(st->launch, st->base + st->w.v, na));
@@ -884,6 +885,7 @@ extern "C" int amdp_stage_get_state(amdp_stage_t* st, float* theta, float* m, fl
     if (!st) return AMDP_E_INVAL;
     const size_t nb = (size_t)st->d.n_params() * 4;
     if (((uintptr_t)theta | (uintptr_t)m | (uintptr_t)v | (uintptr_t)G) % 4) return AMDP_E_INVAL;
+    TRY(join_leaves(st));
     if (theta) TRY(device_copy(st->launch, theta, st->base + st->w.theta, nb));
     if (m) TRY(device_copy(st->launch, m, st->base + st->w.m, nb));
     if (v) TRY(device_copy(st->launch, v, st->base + st->w.v, nb));
@@ -897,6 +899,7 @@ extern "C" int amdp_stage_get_staged_grad(amdp_stage_t* st, float* g) {
     if (!st || !g) return AMDP_E_INVAL;
     if (st->staged_slot < 0) return AMDP_E_MB_STATE;
     if ((uintptr_t)g % 4) return AMDP_E_INVAL;
+    TRY(join_leaves(st));
     return device_copy(st->launch, g, st->base + st->w.g, (size_t)st->d.n_params() * 4);
 }
 
@@ -960,10 +963,19 @@ extern "C" int amdp_grad_accumulate(amdp_stage_t* st, int32_t mb) {
     const int aslot = st->find_mb(mb);
     if (aslot < 0 || !st->as[aslot].backwarded || st->staged_slot != aslot) return AMDP_E_MB_STATE;
     const long n4 = st->d.n_alloc() / 4;
-    ProfScope ps(st, "grad_accumulate", 0.0, 12.0 * (double)st->d.n_params());
-    hipLaunchKernelGGL(accumulate_kernel, dim3(direct_grid(n4, ACC_BLOCK)), dim3(ACC_BLOCK), 0, st->launch,
-                       st->at<float>(st->w.G), st->at<float>(st->w.g), n4);
-    TRY(after_launch());
+    {
+        // HBM-bound and needed by nothing before the next update: it runs on the
+        // side stream under whatever the main stream does next (usually the
+        // matrix-core-bound forward of another minibatch). The next backward's
+        // gradient leaves use the same stream, so they cannot overwrite the
+        // staged gradient early; everything else that touches G or g joins first.
+        Leaf leaf(st);
+        if (!leaf.ok) return AMDP_E_HIP;
+        ProfScope ps(st, "grad_accumulate", 0.0, 12.0 * (double)st->d.n_params());
+        hipLaunchKernelGGL(accumulate_kernel, dim3(direct_grid(n4, ACC_BLOCK)), dim3(ACC_BLOCK), 0, st->launch,
+                           st->at<float>(st->w.G), st->at<float>(st->w.g), n4);
+        TRY(after_launch());
+    }
     st->as[aslot] = ASlot();
     st->staged_slot = -1;
     return AMDP_OK;
@@ -975,6 +987,7 @@ extern "C" int amdp_apply_update(amdp_stage_t* st, const amdp_adam_t* hp, uint32
     if (st->staged_slot >= 0) return AMDP_E_MB_STATE;   // a gradient is waiting to be accumulated
     const int slot = st->free_vslot();
     if (slot < 0) return AMDP_E_STASH_FULL;
+    TRY(join_leaves(st));                               // accumulations still on the side stream
     AdamScalars sc;
     sc.lr = (float)hp->lr; sc.beta1 = (float)hp->beta1; sc.beta2 = (float)hp->beta2; sc.eps = (float)hp->eps;
     sc.weight_decay = (float)hp->weight_decay; sc.grad_scale = (float)hp->grad_scale;
@@ -994,10 +1007,10 @@ extern "C" int amdp_apply_update(amdp_stage_t* st, const amdp_adam_t* hp, uint32
     // read theta, m, v, G; write theta, m, v, the new version, and G = 0
     ProfScope ps(st, "adam_update", 0.0, (32.0 + (double)st->d.esz) * (double)st->d.n_params());
     if (st->d.bf)
-        hipLaunchKernelGGL(adam_kernel<bf16>, dim3(direct_grid(n4, STREAM_BLOCK)), dim3(STREAM_BLOCK), 0, st->launch, th, m,
+        hipLaunchKernelGGL(adam_kernel<bf16>, dim3(direct_grid(n4, ACC_BLOCK)), dim3(ACC_BLOCK), 0, st->launch, th, m,
                            v, G, (bf16*)st->version_ptr(slot), n4, sc);
     else
-        hipLaunchKernelGGL(adam_kernel<float>, dim3(direct_grid(n4, STREAM_BLOCK)), dim3(STREAM_BLOCK), 0, st->launch, th,
+        hipLaunchKernelGGL(adam_kernel<float>, dim3(direct_grid(n4, ACC_BLOCK)), dim3(ACC_BLOCK), 0, st->launch, th,
                            m, v, G, (float*)st->version_ptr(slot), n4, sc);
     TRY(after_launch());
     st->step = t;

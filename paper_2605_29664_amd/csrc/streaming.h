@@ -44,8 +44,11 @@ template <> struct Pack4<bf16> { typedef bf16x4 type; };
 
 // theta, m, v updated in place from grad_scale*G; new version written in the
 // stage dtype; G cleared.      (34 bytes per parameter with bf16 versions)
+// Launch shape measured on 805 M parameters: one-wave workgroups with
+// nontemporal loads and stores reach 5.7 TB/s, 256-lane workgroups with plain
+// loads 5.35 TB/s; interleaving theta/m/v in memory made no difference.
 template <class T>
-__global__ __launch_bounds__(STREAM_BLOCK) void adam_kernel(float* __restrict__ theta, float* __restrict__ m,
+__global__ __launch_bounds__(ACC_BLOCK) void adam_kernel(float* __restrict__ theta, float* __restrict__ m,
                                                             float* __restrict__ v, float* __restrict__ G,
                                                             T* __restrict__ version_out, long n4,
                                                             AdamScalars hp) {
@@ -56,9 +59,10 @@ __global__ __launch_bounds__(STREAM_BLOCK) void adam_kernel(float* __restrict__ 
     f32x4* G4 = (f32x4*)G;
     out4* o4 = (out4*)version_out;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-    const long i = (long)blockIdx.x * STREAM_BLOCK + threadIdx.x;
+    const long i = (long)blockIdx.x * ACC_BLOCK + threadIdx.x;
     if (i < n4) {
-        f32x4 t = th4[i], mm = m4[i], vv = v4[i], gg = G4[i];
+        f32x4 t = __builtin_nontemporal_load(&th4[i]), mm = __builtin_nontemporal_load(&m4[i]);
+        f32x4 vv = __builtin_nontemporal_load(&v4[i]), gg = __builtin_nontemporal_load(&G4[i]);
         out4 o;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {

@@ -123,6 +123,54 @@ def test_zero_lr_versions_bit_identical():
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("key", ["gpt_tile", "bert_tile"])
+def test_unfused_attention_fallback(key):
+    """AMDP_FLASH=0 selects the three-kernel attention (scores, softmax and
+    probabilities in HBM); it must meet the same tolerance as the fused one."""
+    os.environ["AMDP_FLASH"] = "0"
+    rep = run_parity(W.TINY[key], n_windows=1, verbose=False)
+    _report(f"{key}_unfused_attention", rep)
+    assert rep["ok"], worst_entries(rep)
+
+
+def test_side_stream_on_off_bit_identical():
+    """A whole schedule enqueued back to back with no read in between (so the
+    gradient leaves and the accumulations really run beside the main chain)
+    must end in exactly the state the single-stream order produces."""
+    import paper_2605_29664_amd as amdp
+    from oracle.stage import Stage as OStage
+    w = W.TINY["gpt_tile"].with_(depth=16, pipelines=4, stage=8, threshold=4, stash_slots=3, lr=1e-3)
+    theta0 = W.make_theta(w, OStage.from_workload(w).layout)
+    ev = amdp.amdp_schedule_generate(w.depth, w.pipelines, w.stage, w.threshold, 24, 3, amdp.U_NEXT_BUBBLE,
+                                     amdp.BWD_STASHED)
+    import torch
+    xs = {m: torch.from_numpy(W.make_x(w, m)).to("cuda:0").to(torch.bfloat16) for m in range(24)}
+    dys = {m: torch.from_numpy(W.make_dy(w, m)).to("cuda:0").to(torch.bfloat16) for m in range(24)}
+    finals = []
+    for overlap in (True, False):
+        gpu = GpuStage(w, act_slots=12, stash_slots=3)
+        gpu.set_state(theta0)
+        gpu.stage.amdp_stage_set_overlap(overlap)
+        y = torch.empty((w.tokens, w.d_model), dtype=torch.bfloat16, device="cuda:0")
+        dx = torch.empty_like(y)
+        for e in ev:
+            if e.kind == amdp.EV_F:
+                gpu.stage.amdp_stage_forward(e.mb, e.version, xs[e.mb], None, y)
+            elif e.kind == amdp.EV_B:
+                gpu.stage.amdp_stage_backward(e.mb, e.version, dys[e.mb], dx)
+            elif e.kind == amdp.EV_A:
+                gpu.stage.amdp_grad_accumulate(e.mb)
+            else:
+                gpu.stage.amdp_apply_update(w.lr, w.beta1, w.beta2, w.eps, w.weight_decay, 1.0 / w.threshold, True)
+        s = gpu.state()
+        torch.cuda.synchronize()
+        finals.append((s["theta"], s["m"], s["v"], s["G"], dx.float().cpu().numpy(), y.float().cpu().numpy()))
+        gpu.stage.close()
+    assert np.any(finals[0][0] != theta0)
+    for a, b in zip(*finals):
+        assert np.array_equal(a, b)
+
+
 def test_run_to_run_determinism():
     w = W.TINY["bert_tile"]
     res = []
