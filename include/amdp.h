@@ -225,7 +225,11 @@ int amdp_stage_forward(amdp_stage_t* stage, int32_t mb, uint32_t version, const 
 int amdp_stage_backward(amdp_stage_t* stage, int32_t mb, uint32_t version, const void* dY, void* dX);
 
 /* G <- G + g_mb over the flat buffer (Section 3.3); frees the staging buffer
- * and the minibatch's activation slot. */
+ * and the minibatch's activation slot. With the side stream on (see
+ * amdp_stage_set_overlap) the addition runs there, under whatever the caller's
+ * stream does next; every later call that reads or writes G or the staging
+ * buffer (backward, apply_update, get_state, get_staged_grad, set_state) is
+ * ordered after it by the library. */
 int amdp_grad_accumulate(amdp_stage_t* stage, int32_t mb);
 
 typedef struct amdp_adam_t {
@@ -249,8 +253,9 @@ int amdp_apply_update(amdp_stage_t* stage, const amdp_adam_t* hp, uint32_t* new_
 /* Backward enqueues the parameter-gradient work (dW GEMMs, bias and LayerNorm
  * column sums), which is off the dX critical path, on a side stream the stage
  * owns and joins it back into the caller's stream before returning, so the
- * caller still sees one stream. on = 0 keeps everything on the caller's stream
- * (used to time kernels in isolation); default is on. */
+ * caller still sees one stream; amdp_grad_accumulate uses the same side stream.
+ * on = 0 keeps everything on the caller's stream (used to time kernels in
+ * isolation); default is on. Results are bit-identical either way. */
 int amdp_stage_set_overlap(amdp_stage_t* stage, int32_t on);
 
 /* ------------------------------------------------------------------------

@@ -19,12 +19,15 @@
 
 namespace amdp {
 
-// LDS row stride (bytes) of a [rows][DH] bf16 tile that is conflict-free both
-// for 128-bit row reads (16 rows per 16-lane group) and for transposing reads
-// (4 rows x 32 bytes per 16-lane group) with 64 banks x 4 bytes.
-template <int DH> struct AttnTile;
-template <> struct AttnTile<128> { static constexpr int STRIDE = 304; };
-template <> struct AttnTile<64> { static constexpr int STRIDE = 208; };
+// LDS placement of a [rows][DH] bf16 tile that is read both ways: by 128-bit
+// row reads (a 16-lane group reads 16 consecutive rows, 16 bytes each) and by
+// transposing reads (half a wave reads 4 consecutive rows, 64 bytes each).
+// With 64 banks of 4 bytes the first wants the 16 rows 4 banks apart, the
+// second wants the 4 rows 16 banks apart. Both hold when the row stride is
+// DH*2 + 16 bytes (4 banks past a multiple of 32 banks) and, inside every
+// group of 16 rows, row 4a + i is stored at position 4i + a.
+template <int DH> struct AttnTile { static constexpr int STRIDE = DH * 2 + 16; };
+__device__ __forceinline__ int tile_pos(int row) { return (row & ~15) | ((row & 3) << 2) | ((row >> 2) & 3); }
 
 constexpr float LOG2E = 1.4426950408889634f;
 
@@ -39,17 +42,19 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& p, int first) {
 // permuted 16 keys of k-step `ks` inside the 32-row group starting at row r0).
 template <int STRIDE>
 __device__ __forceinline__ bf16x8 frag_tr(lds_u8* tile, int r0, int ks, int c0, int lane) {
+    // rows 16ks + 4h + j (h = lane / 32, j = 0..3) sit at positions 16ks + 4j + h,
+    // the rows 8 further on at positions 2 further on
     const int q = lane >> 4, i = lane & 15;
-    lds_u8* p = tile + (r0 + 16 * ks + 4 * (q >> 1) + (i >> 2)) * STRIDE + (c0 + 16 * (q & 1) + 4 * (i & 3)) * 2;
+    lds_u8* p = tile + (r0 + 16 * ks + 4 * (i >> 2) + (q >> 1)) * STRIDE + (c0 + 16 * (q & 1) + 4 * (i & 3)) * 2;
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * STRIDE));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 2 * STRIDE));
     typedef __attribute__((ext_vector_type(8))) short s16x8;
     return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 // A-operand fragment with rows = 32 consecutive tile rows r0.., k = 16 consecutive columns at 16*kk.
 template <int STRIDE>
 __device__ __forceinline__ bf16x8 frag_row(lds_u8* tile, int r0, int kk, int lane) {
-    return *(lds_bf16x8*)(tile + (r0 + (lane & 31)) * STRIDE + (kk * 16 + 8 * (lane >> 5)) * 2);
+    return *(lds_bf16x8*)(tile + (r0 + tile_pos(lane & 31)) * STRIDE + (kk * 16 + 8 * (lane >> 5)) * 2);
 }
 // Cooperative copy of ROWS x DH bf16 (row stride ld elements in memory) into an
 // LDS tile, split in two so the global loads of the next tile can be in flight
@@ -69,28 +74,46 @@ struct TileCopy {
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             const int v = tid + i * NT, row = v / VPR, c = v % VPR;
-            *(lds_u32x4*)(tile + row * STRIDE + c * 16) = r[i];
+            *(lds_u32x4*)(tile + tile_pos(row) * STRIDE + c * 16) = r[i];
         }
     }
 };
 
+// Work order. The grid is one-dimensional over (128-row block, sequence*head).
+// Under a causal mask a block's work grows with its position, so blocks are
+// numbered heaviest first (rank 0 = most work; the dispatcher hands them out
+// in order as slots free up). When the whole grid is resident at once
+// (total <= resident) that does nothing; there the compute unit that takes
+// block i also takes block i + total/2, so the second half is numbered lightest
+// first and every unit gets a heavy and a light block.
+__device__ __forceinline__ void attn_block(int i, int nq, int nz, int resident, bool causal, int& rank, int& z) {
+    if (!causal) { rank = i % nq; z = i / nq; return; }
+    const int total = nq * nz;
+    int j = i;
+    if (total <= resident && i >= total / 2) j = total - 1 - (i - total / 2);
+    rank = j / nz;
+    z = j % nz;
+}
+
 // ---------------------------------------------------------------- forward
-// grid (s/128, b*H); 4 waves, each owns 32 queries; keys in blocks of 64.
+// grid (s/128) * (b*H) blocks, see attn_block; 4 waves, each owns 32 queries; keys in blocks of 64.
 // qkv: [b*s, 3D] (Q | K | V column blocks, heads of DH); O: [b*s, D];
 // lse2: [b*H, s] = log2-domain log-sum-exp of scale*scores.
 template <int DH, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void flash_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O,
                                                         float* __restrict__ lse2,
                                                         const int32_t* __restrict__ valid_len, int s, int H,
-                                                        int D, float scale_log2e) {
+                                                        int D, float scale_log2e, int nz, int resident) {
     constexpr int STRIDE = AttnTile<DH>::STRIDE, BKV = 64, KQ = DH / 16, DT = DH / 32;
     __shared__ __attribute__((aligned(16))) unsigned char smem[2 * BKV * STRIDE];
     lds_u8* tK = (lds_u8*)smem;
     lds_u8* tV = tK + BKV * STRIDE;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int qb = CAUSAL ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;   // heavy blocks first
-    const int z = blockIdx.y, b = z / H, h = z % H;
+    int rank, z;
+    attn_block(blockIdx.x, s / 128, nz, resident, CAUSAL, rank, z);
+    const int qb = CAUSAL ? s / 128 - 1 - rank : rank;      // late queries see the most keys
+    const int b = z / H, h = z % H;
     const long ld = 3L * D;
     const bf16* base = qkv + (long)b * s * ld + (long)h * DH;
     const int q_blk = qb * 128, q_wave = q_blk + wave * 32, q = q_wave + (lane & 31);
@@ -244,25 +267,27 @@ __device__ __forceinline__ void store_headrow(bf16* row, const f32x16 (&acc)[4],
         }
 }
 
-// dK, dV. grid (s/128, b*H); each wave owns 32 keys (lane % 32) and walks the
+// dK, dV. Same grid; each wave owns 32 keys (lane % 32) and walks the
 // query tiles of 64 that can see them. dqkv: [b*s, 3D], K block at +D, V at +2D.
 template <int DH, bool CAUSAL>
 __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                             const float* __restrict__ lse2,
                                                             const float* __restrict__ delta, bf16* __restrict__ dqkv,
                                                             const int32_t* __restrict__ valid_len, int s, int H,
-                                                            int D, float scale) {
+                                                            int D, float scale, int nz, int resident) {
     constexpr int STRIDE = AttnTile<DH>::STRIDE, BQ = 64, KQ = DH / 16, DT = DH / 32;
     __shared__ __attribute__((aligned(16))) unsigned char smem[2 * BQ * STRIDE];
     __shared__ __attribute__((aligned(16))) float sstat[2][BQ];
     lds_u8* tQ = (lds_u8*)smem;
     lds_u8* tdO = tQ + BQ * STRIDE;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
-    const int z = blockIdx.y, b = z / H, h = z % H;
+    int rank, z;
+    attn_block(blockIdx.x, s / 128, nz, resident, CAUSAL, rank, z);     // early keys are seen by the most queries
+    const int b = z / H, h = z % H;
     const long ld = 3L * D;
     const bf16* base = qkv + (long)b * s * ld + (long)h * DH;
     const bf16* dObase = dO + (long)b * s * D + (long)h * DH;
-    const int k_blk = blockIdx.x * 128, k_wave = k_blk + wave * 32, key = k_wave + (lane & 31);
+    const int k_blk = rank * 128, k_wave = k_blk + wave * 32, key = k_wave + (lane & 31);
     const int klimit = valid_len ? valid_len[b] : s;
     const float sl2 = scale * LOG2E;
 
@@ -340,20 +365,22 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16* __restri
     store_headrow<DT>(out + 2 * D, dv, half, 1.0f);
 }
 
-// dQ. grid (s/128, b*H); each wave owns 32 queries and walks the key blocks of 64 it can see.
+// dQ. Same grid; each wave owns 32 queries and walks the key blocks of 64 it can see.
 template <int DH, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void flash_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                            const float* __restrict__ lse2,
                                                            const float* __restrict__ delta, bf16* __restrict__ dqkv,
                                                            const int32_t* __restrict__ valid_len, int s, int H,
-                                                           int D, float scale) {
+                                                           int D, float scale, int nz, int resident) {
     constexpr int STRIDE = AttnTile<DH>::STRIDE, BKV = 64, KQ = DH / 16, DT = DH / 32;
     __shared__ __attribute__((aligned(16))) unsigned char smem[2 * BKV * STRIDE];
     lds_u8* tK = (lds_u8*)smem;
     lds_u8* tV = tK + BKV * STRIDE;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
-    const int qb = CAUSAL ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
-    const int z = blockIdx.y, b = z / H, h = z % H;
+    int rank, z;
+    attn_block(blockIdx.x, s / 128, nz, resident, CAUSAL, rank, z);
+    const int qb = CAUSAL ? s / 128 - 1 - rank : rank;
+    const int b = z / H, h = z % H;
     const long ld = 3L * D;
     const bf16* base = qkv + (long)b * s * ld + (long)h * DH;
     const int q_blk = qb * 128, q_wave = q_blk + wave * 32, q = q_wave + (lane & 31);

@@ -213,6 +213,7 @@ struct amdp_stage {
     // units the chain's small GEMMs leave idle.
     hipStream_t launch = nullptr;
     hipStream_t side = nullptr;
+    int n_cu = 256;                // compute units of the device
     hipEvent_t events[16] = {};
     int ev_next = 0;
     bool overlap = true;
@@ -415,13 +416,26 @@ GemmArgs attn_batch(const Dims& d) {
 
 inline bool flash_ok(const Dims& d) { return flash_shape_ok(d); }
 
+// Workgroups of 256 lanes of kernel Kern that the whole GPU holds at once.
+template <auto Kern>
+int resident_blocks(int n_cu) {
+    static int per_cu = 0;
+    if (!per_cu) {
+        int v = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, Kern, 256, 0) != hipSuccess || v < 1) v = 1;
+        per_cu = v;
+    }
+    return per_cu * n_cu;
+}
+
 int flash_fwd(amdp_stage* st, const void* qkv, void* o, float* lse2, const int32_t* valid) {
     const Dims& d = st->d;
     const float sc = LOG2E / sqrtf((float)d.dh);
-    dim3 grid(d.s / 128, d.b * d.H);
+    dim3 grid((d.s / 128) * d.b * d.H);
     ProfScope ps(st, "flash_attention_fwd", 4.0 * d.b * d.H * (double)d.s * d.s * d.dh * (d.causal ? (d.s + 1.0) / (2.0 * d.s) : 1.0), 0.0);
 #define FLASH_FWD(DH, C) hipLaunchKernelGGL((flash_fwd_kernel<DH, C>), grid, dim3(256), 0, st->launch, (const bf16*)qkv, \
-                                            (bf16*)o, lse2, valid, d.s, d.H, d.D, sc)
+                                            (bf16*)o, lse2, valid, d.s, d.H, d.D, sc, d.b * d.H,                   \
+                                            resident_blocks<flash_fwd_kernel<DH, C>>(st->n_cu))
     if (d.dh == 128) { if (d.causal) FLASH_FWD(128, true); else FLASH_FWD(128, false); }
     else { if (d.causal) FLASH_FWD(64, true); else FLASH_FWD(64, false); }
 #undef FLASH_FWD
@@ -434,7 +448,7 @@ int flash_bwd(amdp_stage* st, const void* dO, const void* qkv, const void* o, co
     const Dims& d = st->d;
     const float scale = 1.0f / sqrtf((float)d.dh);
     const double unit = 2.0 * d.b * d.H * (double)d.s * d.s * d.dh * (d.causal ? (d.s + 1.0) / (2.0 * d.s) : 1.0);
-    dim3 grid(d.s / 128, d.b * d.H);
+    dim3 grid((d.s / 128) * d.b * d.H);
     {
         ProfScope ps(st, "attention_delta", 0.0, 2.0 * d.N * d.D * 2.0);
         if (d.dh == 128)
@@ -446,7 +460,8 @@ int flash_bwd(amdp_stage* st, const void* dO, const void* qkv, const void* o, co
         TRY(after_launch());
     }
 #define FLASH_BWD(KERN, DH, C) hipLaunchKernelGGL((KERN<DH, C>), grid, dim3(256), 0, st->launch, (const bf16*)qkv, \
-                                                  (const bf16*)dO, lse2, (const float*)delta, (bf16*)dqkv, valid, d.s, d.H, d.D, scale)
+                                                  (const bf16*)dO, lse2, (const float*)delta, (bf16*)dqkv, valid, d.s, d.H, d.D, scale, \
+                                                  d.b * d.H, resident_blocks<KERN<DH, C>>(st->n_cu))
     {
         ProfScope ps(st, "flash_attention_bwd_dkdv", 4.0 * unit, 0.0);   // S, dP, dV, dK
         if (d.dh == 128) { if (d.causal) FLASH_BWD(flash_bwd_dkv_kernel, 128, true); else FLASH_BWD(flash_bwd_dkv_kernel, 128, false); }
@@ -822,6 +837,12 @@ extern "C" int amdp_stage_create(const amdp_stage_config_t* cfg, void* workspace
     if (workspace_bytes < st->w.total) { delete st; return AMDP_E_INVAL; }
     st->base = (char*)workspace;
     st->stream = (hipStream_t)hip_stream;
+    {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            st->n_cu = cus;
+    }
     st->launch = st->stream;
     st->n_vslots = cfg->stash_slots + 1;
     const char* ov = getenv("AMDP_OVERLAP");
