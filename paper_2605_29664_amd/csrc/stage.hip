@@ -305,41 +305,48 @@ inline double gemm_flops(const GemmArgs& g) {
 }
 
 // ---- GEMM dispatch ----------------------------------------------------------
+template <int BM, int BN, bool A_KM, bool B_KM, int WGN = 2>
+hipError_t launch_tile(amdp_stage* st, const GemmArgs& g) {
+    return st->use_tr ? launch_gemm_mfma_inst<BM, BN, A_KM, B_KM, true, WGN>(g, st->launch)
+                      : launch_gemm_mfma_inst<BM, BN, A_KM, B_KM, false, WGN>(g, st->launch);
+}
+
+// Tile choice, from measurement on MI355X: the largest tile that still gives
+// at least 192 workgroups (three quarters of the compute units) wins; when no
+// tile gets there, the one with the most workgroups does.
 template <bool A_KM, bool B_KM>
 int gemm_bf16_layout(amdp_stage* st, const GemmArgs& g) {
-    const long tiles256 = (long)(g.M / 256) * (g.N / 256) * g.batch;
-    const bool ok256 = mfma_shape_ok<256, 256>(g, A_KM, B_KM);
-    const bool ok128 = mfma_shape_ok<128, 128>(g, A_KM, B_KM);
-    const bool ok64 = mfma_shape_ok<128, 64>(g, A_KM, B_KM);
-    hipError_t e;
-    const bool tr = st->use_tr;
-    int tile = 0;
-    if (ok256 && (tiles256 >= 192 || !ok128)) tile = 256;
-    else if (ok128) tile = 128;
-    else if (ok64) tile = 64;
-    if (st->force_tile == 128 && ok128) tile = 128;
-    if (st->force_tile == 256 && ok256) tile = 256;
-    if (st->force_tile < 0) tile = 0;
+    struct Cand { int bm, bn; bool ok; };
+    const Cand cand[5] = {{256, 256, mfma_shape_ok<256, 256>(g, A_KM, B_KM)}, {128, 128, mfma_shape_ok<128, 128>(g, A_KM, B_KM)},
+                          {128, 64, mfma_shape_ok<128, 64>(g, A_KM, B_KM)},   {64, 128, mfma_shape_ok<64, 128>(g, A_KM, B_KM)},
+                          {64, 64, mfma_shape_ok<64, 64>(g, A_KM, B_KM)}};
+    auto tiles = [&](const Cand& c) { return (long)(g.M / c.bm) * (g.N / c.bn) * g.batch; };
+    int pick = -1;
+    for (int i = 0; i < 5 && pick < 0; ++i)
+        if (cand[i].ok && tiles(cand[i]) >= 192) pick = i;
+    if (pick < 0)
+        for (int i = 0; i < 5; ++i)
+            if (cand[i].ok && (pick < 0 || tiles(cand[i]) > tiles(cand[pick]))) pick = i;
+    if (st->force_tile > 0)
+        for (int i = 0; i < 5; ++i)
+            if (cand[i].ok && (cand[i].bm * 1000 + cand[i].bn == st->force_tile ||
+                               (cand[i].bm == cand[i].bn && cand[i].bm == st->force_tile))) pick = i;
+    if (st->force_tile < 0) pick = -1;
     char name[48];
-    snprintf(name, sizeof(name), "gemm_%s_%s%s", tile == 256 ? "mfma256x256" : tile == 128 ? "mfma128x128"
-             : tile == 64 ? "mfma128x64" : "generic", A_KM ? "TN" : (B_KM ? "NN" : "NT"), g.batch > 1 ? "_batched" : "");
+    if (pick >= 0)
+        snprintf(name, sizeof(name), "gemm_mfma%dx%d_%s%s", cand[pick].bm, cand[pick].bn,
+                 A_KM ? "TN" : (B_KM ? "NN" : "NT"), g.batch > 1 ? "_batched" : "");
+    else
+        snprintf(name, sizeof(name), "gemm_generic_%s%s", A_KM ? "TN" : (B_KM ? "NN" : "NT"), g.batch > 1 ? "_batched" : "");
     ProfScope ps(st, name, gemm_flops(g), 0.0);
-    switch (tile) {
-        case 256:
-            // eight waves (two per SIMD), each 128x64 of the tile
-            e = tr ? launch_gemm_mfma_inst<256, 256, A_KM, B_KM, true, 4>(g, st->launch)
-                   : launch_gemm_mfma_inst<256, 256, A_KM, B_KM, false, 4>(g, st->launch);
-            break;
-        case 128:
-            e = tr ? launch_gemm_mfma_inst<128, 128, A_KM, B_KM, true>(g, st->launch)
-                   : launch_gemm_mfma_inst<128, 128, A_KM, B_KM, false>(g, st->launch);
-            break;
-        case 64:
-            e = tr ? launch_gemm_mfma_inst<128, 64, A_KM, B_KM, true>(g, st->launch)
-                   : launch_gemm_mfma_inst<128, 64, A_KM, B_KM, false>(g, st->launch);
-            break;
-        default:
-            e = launch_gemm_simple<bf16>(g, st->launch);
+    hipError_t e;
+    switch (pick) {
+        case 0: e = launch_tile<256, 256, A_KM, B_KM, 4>(st, g); break;   // eight waves (two per SIMD), each 128x64 of the tile
+        case 1: e = launch_tile<128, 128, A_KM, B_KM>(st, g); break;
+        case 2: e = launch_tile<128, 64, A_KM, B_KM>(st, g); break;
+        case 3: e = launch_tile<64, 128, A_KM, B_KM>(st, g); break;
+        case 4: e = launch_tile<64, 64, A_KM, B_KM>(st, g); break;
+        default: e = launch_gemm_simple<bf16>(g, st->launch);
     }
     return hip_ok(e, name) ? AMDP_OK : AMDP_E_HIP;
 }

@@ -29,6 +29,20 @@ def test_full_width_one_layer(k):
     assert rep["ok"], worst_entries(rep)
 
 
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("key", ["paper_gpt_h1600", "paper_bert_h1600"])
+def test_paper_shaped_one_layer(key):
+    """Hidden size 1600 (Table 2): multiples of 64 that are not multiples of
+    128, 25 heads of 64 (fused attention) or 32 heads of 50 (unfused attention
+    on the generic kernels, heads not 16-byte aligned)."""
+    w = W.PAPER[key].with_(n_layers=1)
+    print(f"\n[{key} one layer at full width] start", flush=True)
+    rep = run_parity(w, threshold=1, n_minibatches=1, verbose=True,
+                     cfg_kw=dict(act_slots=1, stash_slots=1))
+    print(f"[{key} one layer] worst={rep['worst']:.3e} {rep['seconds']:.0f}s", worst_entries(rep, 4), flush=True)
+    assert rep["ok"], worst_entries(rep)
+
+
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("k,prefix", [(2, 1024), (3, 512), (5, 256)])
 def test_full_depth_forward_one_sequence(k, prefix):

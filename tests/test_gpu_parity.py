@@ -77,6 +77,23 @@ def test_tile_bf16_head_dim_128(key):
     assert rep["ok"], worst_entries(rep)
 
 
+@pytest.mark.parametrize("tile", ["256", "128", "128064", "64128", "64"])
+def test_tile_bf16_forced_tile(tile):
+    """Every matrix-core tile shape on the same workload (a tile that does not
+    divide a product's shape leaves that product to the default choice)."""
+    os.environ["AMDP_GEMM_TILE"] = tile
+    rep = run_parity(W.TINY["gpt_tile"], n_windows=1, verbose=False)
+    _report(f"gpt_tile_forced_{tile}", rep)
+    assert rep["ok"], worst_entries(rep)
+
+
+@pytest.mark.parametrize("key", ["gpt_tile64", "bert_dh50"])
+def test_bf16_multiples_of_64_and_head_dim_50(key):
+    rep = run_parity(W.TINY[key], n_windows=1, verbose=False)
+    _report(key, rep)
+    assert rep["ok"], worst_entries(rep)
+
+
 def test_tile_bf16_generic_kernels_agree():
     os.environ["AMDP_GEMM_TILE"] = "-1"
     rep = run_parity(W.TINY["gpt_tile"], n_windows=1, verbose=False)

@@ -106,9 +106,26 @@ TINY = {
                                  depth=4, pipelines=2, stage=1, threshold=4),
     "bert_tile128": StageWorkload("tile_bert_dh128", 21, BERT_POSTLN_BIDIR, 1, 256, 2, 512, 384, 2, BF16,
                                   depth=4, pipelines=2, stage=1, threshold=4),
+    # multiples of 64 but not of 128: the 64-row matrix tiles
+    "gpt_tile64": StageWorkload("tile64_gpt", 22, GPT_PRELN_CAUSAL, 2, 192, 3, 768, 128, 2, BF16,
+                                depth=4, pipelines=2, stage=1, threshold=4),
+    # head dimension 50 (the paper's BERT-style width / heads): no fused attention, unaligned heads
+    "bert_dh50": StageWorkload("tiny_bert_dh50", 23, BERT_POSTLN_BIDIR, 1, 400, 8, 800, 24, 2, BF16,
+                               depth=4, pipelines=2, stage=1, threshold=4),
     "lmhead_tile": StageWorkload("tile_lmhead", 19, GPT_PRELN_CAUSAL, 1, 256, 4, 1024, 256, 2, BF16,
                                  has_lm_head=True, vocab=1931,
                                  depth=4, pipelines=2, stage=3, threshold=4),
+}
+
+
+# Stages shaped like the paper's own models (Table 2: hidden 1600; 25 heads for
+# the GPT-style model, 32 for the BERT-style one; sequence 1024, microbatch 4;
+# 48 layers over a depth-8 pipeline = 6 layers per stage).
+PAPER = {
+    "paper_gpt_h1600": StageWorkload("paper_gpt_h1600_bf16", 31, GPT_PRELN_CAUSAL, 6, 1600, 25, 6400, 1024, 4, BF16,
+                                     depth=8, pipelines=4, stage=4, threshold=8),
+    "paper_bert_h1600": StageWorkload("paper_bert_h1600_bf16", 32, BERT_POSTLN_BIDIR, 6, 1600, 32, 6400, 1024, 4, BF16,
+                                      depth=8, pipelines=4, stage=4, threshold=8),
 }
 
 
@@ -117,6 +134,8 @@ def get(key):
         return CONFIGS[key]
     if key in TINY:
         return TINY[key]
+    if key in PAPER:
+        return PAPER[key]
     if key.isdigit():
         return CONFIGS[int(key)]
     for c in CONFIGS.values():
