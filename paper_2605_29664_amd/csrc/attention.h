@@ -231,6 +231,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
 }
 
 
+// Head-wise repacking between widths (32-bit pairs of bf16): output pair i of
+// `pairs` belongs to chunk i / wd2 and column pair i % wd2; columns past the
+// source width read as zero.
+__global__ __launch_bounds__(256) void repack_heads_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst,
+                                                           long pairs, int ws2, int wd2) {
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= pairs) return;
+    const long chunk = i / wd2;
+    const int c = (int)(i % wd2);
+    dst[i] = c < ws2 ? src[chunk * ws2 + c] : 0u;
+}
+
 // ---------------------------------------------------------------- backward
 // delta[z][q] = sum_d dO[q, h*DH + d] * O[q, h*DH + d]   (z = sequence*H + head)
 // One wave per token row; a head's DH/8 vectors sit in DH/8 adjacent lanes.

@@ -111,6 +111,7 @@ struct Carve {
     struct BwdScratch { size_t t_a, t_b, t_c, dffn, dqkv, dxout; };
     std::vector<BwdScratch> bw;
     size_t lm_dz, lm_dy, dO, dP, partial, row_loss, total;
+    size_t pk_qkv = 0, pk_dqkv = 0, pk_o = 0, pk_do = 0;   // head-padded copies for the fused attention
     int partial_chunks;
     SlotLayout slot;
 };
@@ -123,7 +124,13 @@ inline int flash_mode() {
     const char* e = getenv("AMDP_FLASH");
     return e ? atoi(e) : 1;
 }
-inline bool flash_shape_ok(const Dims& d) { return d.bf && (d.dh == 64 || d.dh == 128) && d.s % 128 == 0; }
+// The fused attention kernels exist for head dimensions 64 and 128. Other even
+// head dimensions up to 128 run through them zero-padded: Q, K, V (and dO, O in
+// backward) are repacked head by head into scratch with the padded width, which
+// changes no result (the padding contributes exact zeros to every product).
+inline int flash_head_dim(const Dims& d) { return d.dh <= 64 ? 64 : 128; }
+inline bool flash_shape_ok(const Dims& d) { return d.bf && d.dh <= 128 && d.dh % 2 == 0 && d.s % 128 == 0; }
+inline bool flash_packed(const Dims& d) { return d.dh != flash_head_dim(d); }
 
 void carve(const Dims& d, const amdp_stage_config_t& c, Carve* w) {
     size_t off = 0;
@@ -166,6 +173,11 @@ void carve(const Dims& d, const amdp_stage_config_t& c, Carve* w) {
     w->lm_dy = take(d.lm ? ND : 0);
     w->dO = take(ND);
     w->dP = take(PP);
+    {
+        const bool pk = fused && flash_packed(d);
+        const size_t NDp = pk ? (size_t)d.N * d.H * flash_head_dim(d) * d.esz : 0;
+        w->pk_qkv = take(3 * NDp); w->pk_dqkv = take(3 * NDp); w->pk_o = take(NDp); w->pk_do = take(NDp);
+    }
     w->partial_chunks = 64;
     const size_t maxw = (size_t)std::max(std::max(3 * d.D, d.F), 2 * d.D);
     w->partial = take((size_t)w->partial_chunks * maxw * 4);
@@ -435,54 +447,94 @@ int resident_blocks(int n_cu) {
     return per_cu * n_cu;
 }
 
-int flash_fwd(amdp_stage* st, const void* qkv, void* o, float* lse2, const int32_t* valid) {
+// dst[r][j][0..w_dst) = src[r][j][0..w_src) cut or zero-padded to w_dst, for
+// `chunks` head-sized column blocks per row (both widths even).
+int repack_heads(amdp_stage* st, const void* src, void* dst, long rows, int chunks, int w_src, int w_dst) {
+    const long pairs = rows * chunks * (w_dst / 2);
+    ProfScope ps(st, "attention_repack_heads", 0.0, 2.0 * rows * chunks * (double)(w_src < w_dst ? w_src + w_dst : 2 * w_dst));
+    hipLaunchKernelGGL(repack_heads_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, st->launch,
+                       (const uint32_t*)src, (uint32_t*)dst, pairs, w_src / 2, w_dst / 2);
+    return after_launch();
+}
+
+// qkv [N, 3*Dk], o [N, Dk] with heads of DHK = 64 or 128 columns (Dk = H*DHK)
+int flash_fwd_launch(amdp_stage* st, const void* qkv, void* o, float* lse2, const int32_t* valid, int dhk) {
     const Dims& d = st->d;
     const float sc = LOG2E / sqrtf((float)d.dh);
+    const int Dk = d.H * dhk;
     dim3 grid((d.s / 128) * d.b * d.H);
     ProfScope ps(st, "flash_attention_fwd", 4.0 * d.b * d.H * (double)d.s * d.s * d.dh * (d.causal ? (d.s + 1.0) / (2.0 * d.s) : 1.0), 0.0);
 #define FLASH_FWD(DH, C) hipLaunchKernelGGL((flash_fwd_kernel<DH, C>), grid, dim3(256), 0, st->launch, (const bf16*)qkv, \
-                                            (bf16*)o, lse2, valid, d.s, d.H, d.D, sc, d.b * d.H,                   \
+                                            (bf16*)o, lse2, valid, d.s, d.H, Dk, sc, d.b * d.H,                     \
                                             resident_blocks<flash_fwd_kernel<DH, C>>(st->n_cu))
-    if (d.dh == 128) { if (d.causal) FLASH_FWD(128, true); else FLASH_FWD(128, false); }
+    if (dhk == 128) { if (d.causal) FLASH_FWD(128, true); else FLASH_FWD(128, false); }
     else { if (d.causal) FLASH_FWD(64, true); else FLASH_FWD(64, false); }
 #undef FLASH_FWD
     return after_launch();
 }
 
+int flash_fwd(amdp_stage* st, const void* qkv, void* o, float* lse2, const int32_t* valid) {
+    const Dims& d = st->d;
+    const int dhk = flash_head_dim(d);
+    if (!flash_packed(d)) return flash_fwd_launch(st, qkv, o, lse2, valid, dhk);
+    void* pq = st->at<>(st->w.pk_qkv);
+    void* po = st->at<>(st->w.pk_o);
+    TRY(repack_heads(st, qkv, pq, d.N, 3 * d.H, d.dh, dhk));
+    TRY(flash_fwd_launch(st, pq, po, lse2, valid, dhk));
+    return repack_heads(st, po, o, d.N, d.H, dhk, d.dh);
+}
+
 // delta, dK/dV and dQ kernels; lse2 is what flash_fwd saved, delta is scratch [b*H*s] fp32
-int flash_bwd(amdp_stage* st, const void* dO, const void* qkv, const void* o, const float* lse2, float* delta,
-              void* dqkv, const int32_t* valid) {
+int flash_bwd_launch(amdp_stage* st, const void* dO, const void* qkv, const void* o, const float* lse2, float* delta,
+                     void* dqkv, const int32_t* valid, int dhk) {
     const Dims& d = st->d;
     const float scale = 1.0f / sqrtf((float)d.dh);
+    const int Dk = d.H * dhk;
     const double unit = 2.0 * d.b * d.H * (double)d.s * d.s * d.dh * (d.causal ? (d.s + 1.0) / (2.0 * d.s) : 1.0);
     dim3 grid((d.s / 128) * d.b * d.H);
     {
         ProfScope ps(st, "attention_delta", 0.0, 2.0 * d.N * d.D * 2.0);
-        if (d.dh == 128)
+        if (dhk == 128)
             hipLaunchKernelGGL(attn_delta_kernel<128>, dim3((d.N + 3) / 4), dim3(256), 0, st->launch, (const bf16*)dO,
-                               (const bf16*)o, delta, d.N, d.s, d.H, d.D);
+                               (const bf16*)o, delta, d.N, d.s, d.H, Dk);
         else
             hipLaunchKernelGGL(attn_delta_kernel<64>, dim3((d.N + 3) / 4), dim3(256), 0, st->launch, (const bf16*)dO,
-                               (const bf16*)o, delta, d.N, d.s, d.H, d.D);
+                               (const bf16*)o, delta, d.N, d.s, d.H, Dk);
         TRY(after_launch());
     }
 #define FLASH_BWD(KERN, DH, C) hipLaunchKernelGGL((KERN<DH, C>), grid, dim3(256), 0, st->launch, (const bf16*)qkv, \
-                                                  (const bf16*)dO, lse2, (const float*)delta, (bf16*)dqkv, valid, d.s, d.H, d.D, scale, \
+                                                  (const bf16*)dO, lse2, (const float*)delta, (bf16*)dqkv, valid, d.s, d.H, Dk, scale, \
                                                   d.b * d.H, resident_blocks<KERN<DH, C>>(st->n_cu))
     {
         ProfScope ps(st, "flash_attention_bwd_dkdv", 4.0 * unit, 0.0);   // S, dP, dV, dK
-        if (d.dh == 128) { if (d.causal) FLASH_BWD(flash_bwd_dkv_kernel, 128, true); else FLASH_BWD(flash_bwd_dkv_kernel, 128, false); }
+        if (dhk == 128) { if (d.causal) FLASH_BWD(flash_bwd_dkv_kernel, 128, true); else FLASH_BWD(flash_bwd_dkv_kernel, 128, false); }
         else { if (d.causal) FLASH_BWD(flash_bwd_dkv_kernel, 64, true); else FLASH_BWD(flash_bwd_dkv_kernel, 64, false); }
         TRY(after_launch());
     }
     {
         ProfScope ps(st, "flash_attention_bwd_dq", 1.0 * unit, 0.0);     // dQ (S and dP are recomputed, not counted)
-        if (d.dh == 128) { if (d.causal) FLASH_BWD(flash_bwd_dq_kernel, 128, true); else FLASH_BWD(flash_bwd_dq_kernel, 128, false); }
+        if (dhk == 128) { if (d.causal) FLASH_BWD(flash_bwd_dq_kernel, 128, true); else FLASH_BWD(flash_bwd_dq_kernel, 128, false); }
         else { if (d.causal) FLASH_BWD(flash_bwd_dq_kernel, 64, true); else FLASH_BWD(flash_bwd_dq_kernel, 64, false); }
         TRY(after_launch());
     }
 #undef FLASH_BWD
     return AMDP_OK;
+}
+
+int flash_bwd(amdp_stage* st, const void* dO, const void* qkv, const void* o, const float* lse2, float* delta,
+              void* dqkv, const int32_t* valid) {
+    const Dims& d = st->d;
+    const int dhk = flash_head_dim(d);
+    if (!flash_packed(d)) return flash_bwd_launch(st, dO, qkv, o, lse2, delta, dqkv, valid, dhk);
+    void* pq = st->at<>(st->w.pk_qkv);
+    void* po = st->at<>(st->w.pk_o);
+    void* pdo = st->at<>(st->w.pk_do);
+    void* pdq = st->at<>(st->w.pk_dqkv);
+    TRY(repack_heads(st, qkv, pq, d.N, 3 * d.H, d.dh, dhk));
+    TRY(repack_heads(st, o, po, d.N, d.H, d.dh, dhk));
+    TRY(repack_heads(st, dO, pdo, d.N, d.H, d.dh, dhk));
+    TRY(flash_bwd_launch(st, pdo, pq, po, lse2, delta, pdq, valid, dhk));
+    return repack_heads(st, pdq, dqkv, d.N, 3 * d.H, dhk, d.dh);
 }
 
 template <class T>

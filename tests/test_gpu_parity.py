@@ -87,8 +87,8 @@ def test_tile_bf16_forced_tile(tile):
     assert rep["ok"], worst_entries(rep)
 
 
-@pytest.mark.parametrize("key", ["gpt_tile64", "bert_dh50"])
-def test_bf16_multiples_of_64_and_head_dim_50(key):
+@pytest.mark.parametrize("key", ["gpt_tile64", "bert_dh50", "bert_tile_dh50", "gpt_tile_dh96"])
+def test_bf16_multiples_of_64_and_odd_head_dims(key):
     rep = run_parity(W.TINY[key], n_windows=1, verbose=False)
     _report(key, rep)
     assert rep["ok"], worst_entries(rep)

@@ -112,6 +112,11 @@ TINY = {
     # head dimension 50 (the paper's BERT-style width / heads): no fused attention, unaligned heads
     "bert_dh50": StageWorkload("tiny_bert_dh50", 23, BERT_POSTLN_BIDIR, 1, 400, 8, 800, 24, 2, BF16,
                                depth=4, pipelines=2, stage=1, threshold=4),
+    # head dimensions the fused attention reaches by zero-padding (50 -> 64, 96 -> 128)
+    "bert_tile_dh50": StageWorkload("tile_bert_dh50", 24, BERT_POSTLN_BIDIR, 1, 400, 8, 800, 128, 2, BF16,
+                                    depth=4, pipelines=2, stage=1, threshold=4),
+    "gpt_tile_dh96": StageWorkload("tile_gpt_dh96", 25, GPT_PRELN_CAUSAL, 1, 192, 2, 384, 256, 1, BF16,
+                                   depth=4, pipelines=2, stage=1, threshold=4),
     "lmhead_tile": StageWorkload("tile_lmhead", 19, GPT_PRELN_CAUSAL, 1, 256, 4, 1024, 256, 2, BF16,
                                  has_lm_head=True, vocab=1931,
                                  depth=4, pipelines=2, stage=3, threshold=4),
