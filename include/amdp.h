@@ -206,7 +206,9 @@ int amdp_stage_resident_versions(amdp_stage_t* stage, uint32_t* versions, int32_
  * version is whatever the schedule assigns; it must be resident).
  *   X    device [N, D] token-major (row = sequence*s + position), stage dtype
  *   aux  device int32: valid_len[b] for the BERT block (keys at positions >=
- *        valid_len are masked), targets[N] on an LM-head stage, else NULL
+ *        valid_len are masked; each entry in [1, s] -- a sequence with no
+ *        visible key has no softmax and the library does not check device
+ *        data), targets[N] in [0, V) on an LM-head stage, else NULL
  *   out  device: Y [N, D] in the stage dtype, or one fp32 (the mean
  *        cross-entropy) on an LM-head stage
  * Saves the activations backward needs in a free activation slot and pins

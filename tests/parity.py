@@ -111,7 +111,8 @@ class GpuStage:
 
 
 def run_parity(w, n_windows=2, policy=OSched.STASHED, placement=OSched.NEXT_BUBBLE, inject_limit=None,
-               threshold=None, n_minibatches=None, verbose=True, tol=None, cfg_kw=None, device="cuda:0"):
+               threshold=None, n_minibatches=None, verbose=True, tol=None, cfg_kw=None, device="cuda:0",
+               aux_fn=None):
     """Runs M = n_windows*T + w*P minibatches through library and oracle.
     Returns {'ok', 'worst', 'details': [(event, name, err)], ...}."""
     import paper_2605_29664_amd as amdp
@@ -151,7 +152,7 @@ def run_parity(w, n_windows=2, policy=OSched.STASHED, placement=OSched.NEXT_BUBB
         if verbose:
             print(f"  {OSched.KIND_NAMES[ev.kind]}{ev.mb} ...", flush=True)
         if ev.kind == amdp.EV_F:
-            x, aux = W.make_x(w, ev.mb), aux_for(w, ev.mb)
+            x, aux = W.make_x(w, ev.mb), (aux_fn or aux_for)(w, ev.mb)
             ref = orun.forward(ev.mb, ev.version, x, aux)
             got = gpu.forward(ev.mb, ev.version, x, aux)
             note(ev, "loss" if w.has_lm_head else "Y", rel_err(got, ref))

@@ -94,6 +94,30 @@ def test_bf16_multiples_of_64_and_odd_head_dims(key):
     assert rep["ok"], worst_entries(rep)
 
 
+@pytest.mark.parametrize("key", ["bert_tile", "bert_mid"])
+def test_padding_mask_extremes(key):
+    """Valid lengths at the ends of their range and on key-block boundaries:
+    one visible key, a whole sequence, exactly one block of 64, one past it."""
+    w = W.TINY[key]
+    pool = [1, w.seq_len, 64, 65, 2, w.seq_len - 1, 128, 63]
+    def aux(w_, mb):
+        return np.array([min(pool[(mb * w_.microbatch + i) % len(pool)], w_.seq_len) for i in range(w_.microbatch)],
+                        dtype=np.int32)
+    rep = run_parity(w, n_windows=1, verbose=False, aux_fn=aux)
+    _report(f"{key}_mask_extremes", rep)
+    assert rep["ok"], worst_entries(rep)
+
+
+@pytest.mark.parametrize("d,P,i,T,M", [(1, 1, 0, 1, 3), (2, 1, 1, 1, 1), (4, 2, 3, 3, 7), (6, 3, 0, 4, 10)])
+def test_degenerate_schedules(d, P, i, T, M):
+    """One stage / one pipeline, an update after every minibatch, a single
+    minibatch, a last partial window."""
+    w = W.TINY["gpt_tile"].with_(depth=d, pipelines=P, stage=i, threshold=T, n_layers=1)
+    rep = run_parity(w, n_minibatches=M, verbose=False)
+    _report(f"degenerate_d{d}P{P}i{i}T{T}M{M}", rep)
+    assert rep["ok"] and rep["events"] == 3 * M + -(-M // T), worst_entries(rep)
+
+
 def test_tile_bf16_generic_kernels_agree():
     os.environ["AMDP_GEMM_TILE"] = "-1"
     rep = run_parity(W.TINY["gpt_tile"], n_windows=1, verbose=False)
