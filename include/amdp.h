@@ -260,6 +260,14 @@ int amdp_apply_update(amdp_stage_t* stage, const amdp_adam_t* hp, uint32_t* new_
  * isolation); default is on. Results are bit-identical either way. */
 int amdp_stage_set_overlap(amdp_stage_t* stage, int32_t on);
 
+/* Orders everything the stage has enqueued on its own side stream (at most the
+ * accumulations since the last join) before whatever the caller enqueues next
+ * on its stream. Needed only by a caller that wants a point where the stage's
+ * stream alone carries all of its work: before ending a HIP-graph capture that
+ * contains amdp_grad_accumulate, or before reusing the workspace for something
+ * else. Enqueues an event wait; does not block the host. */
+int amdp_stage_join(amdp_stage_t* stage);
+
 /* ------------------------------------------------------------------------
  * Measurement aid: per-kernel-class device time from HIP events recorded on
  * the stage's stream around every launch between begin and end. `flops` and

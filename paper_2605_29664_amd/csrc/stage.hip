@@ -1141,9 +1141,15 @@ extern "C" int amdp_stage_profile_end(amdp_stage_t* st, amdp_profile_entry_t* ou
 
 extern "C" const char* amdp_last_hip_error(void) { return g_hip_detail; }
 
+extern "C" int amdp_stage_join(amdp_stage_t* st) {
+    if (!st) return AMDP_E_INVAL;
+    return join_leaves(st);
+}
+
 extern "C" int amdp_stage_set_overlap(amdp_stage_t* st, int32_t on) {
     if (!st) return AMDP_E_INVAL;
     if (on && !st->side) return AMDP_E_INVAL;   // the stage was created without a side stream
+    TRY(join_leaves(st));                       // work still on the side stream stays ordered
     st->overlap = on != 0;
     return AMDP_OK;
 }

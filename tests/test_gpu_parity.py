@@ -212,6 +212,69 @@ def test_side_stream_on_off_bit_identical():
         assert np.array_equal(a, b)
 
 
+def test_hip_graph_replay_matches_eager():
+    """Forward + backward + accumulate captured once in a HIP graph (the library
+    clears and copies with its own kernels and forks / joins its side stream
+    with events, all of which a capture records) and replayed three times with
+    eager work and synchronisation in between must reproduce, bit for bit, the
+    eager results: Y, dX, and G after one, two and three accumulations."""
+    import torch
+    import paper_2605_29664_amd as amdp
+    from tests.parity import make_cfg
+    w = W.TINY["gpt_tile"]
+    dev = torch.device("cuda:0")
+    cfg = make_cfg(w, act_slots=2, stash_slots=1)
+    theta0 = torch.from_numpy(W.make_theta(w, amdp.amdp_stage_param_layout(cfg))).to(dev)
+    s = torch.cuda.Stream(device=dev)
+    dt = torch.bfloat16
+    xs = [torch.from_numpy(W.make_x(w, k)).to(dev).to(dt) for k in (0, 1, 0)]
+    dy = torch.from_numpy(W.make_dy(w, 0)).to(dev).to(dt)
+
+    def fresh():
+        st = amdp.Stage(cfg, device="cuda:0", stream=s)
+        with torch.cuda.stream(s):
+            st.amdp_stage_set_state(theta0)
+        s.synchronize()
+        return st
+
+    def fba(st, X, Y, dX):
+        st.amdp_stage_forward(0, 0, X, None, Y)
+        st.amdp_stage_backward(0, 0, dy, dX)
+        st.amdp_grad_accumulate(0)
+        st.amdp_stage_join()            # the accumulation runs on the stage's side stream
+
+    def read_G(st):
+        G = torch.empty(st.n_params, dtype=torch.float32, device=dev)
+        with torch.cuda.stream(s):
+            st.amdp_stage_get_state(None, None, None, G)
+        s.synchronize()
+        return G
+
+    st = fresh()
+    Y, dX, ref = torch.empty_like(xs[0]), torch.empty_like(xs[0]), []
+    for X in xs:
+        with torch.cuda.stream(s):
+            fba(st, X, Y, dX)
+        s.synchronize()
+        ref.append((Y.clone(), dX.clone(), read_G(st)))
+    st.close()
+
+    st = fresh()                        # same process: kernel attributes and occupancy queries are cached
+    Xs = xs[0].clone()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        fba(st, Xs, Y, dX)
+    for k, X in enumerate(xs):
+        Xs.copy_(X)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = (Y, dX, read_G(st))
+        for name, a, b in zip(("Y", "dX", "G"), got, ref[k]):
+            assert torch.equal(a, b), f"replay {k}: {name} differs from the eager run"
+    st.close()
+
+
 def test_run_to_run_determinism():
     w = W.TINY["bert_tile"]
     res = []
