@@ -354,7 +354,13 @@ int gemm_bf16_layout(amdp_stage* st, const GemmArgs& g) {
     hipError_t e;
     switch (pick) {
         case 0: e = launch_tile<256, 256, A_KM, B_KM, 4>(st, g); break;   // eight waves (two per SIMD), each 128x64 of the tile
-        case 1: e = launch_tile<128, 128, A_KM, B_KM>(st, g); break;
+        case 1:
+            // up to one workgroup per compute unit: eight waves (two per SIMD, each
+            // 64x32 of the tile) hide latency that a second resident workgroup would
+            // otherwise hide; measured 9-14 % faster there, 2-5 % slower beyond
+            e = tiles(cand[1]) <= st->n_cu ? launch_tile<128, 128, A_KM, B_KM, 4>(st, g)
+                                           : launch_tile<128, 128, A_KM, B_KM>(st, g);
+            break;
         case 2: e = launch_tile<128, 64, A_KM, B_KM>(st, g); break;
         case 3: e = launch_tile<64, 128, A_KM, B_KM>(st, g); break;
         case 4: e = launch_tile<64, 64, A_KM, B_KM>(st, g); break;
