@@ -302,6 +302,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16* __restri
     const int k_blk = rank * 128, k_wave = k_blk + wave * 32, key = k_wave + (lane & 31);
     const int klimit = valid_len ? valid_len[b] : s;
     const float sl2 = scale * LOG2E;
+    const bool key_dead = key >= klimit;     // padding: this lane's key is visible to nobody
 
     bf16x8 bk[KQ], bv[KQ];      // B operands: n = key, k = head dimension
 #pragma unroll
@@ -356,9 +357,9 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16* __restri
                     const int v = 4 * gq + e;
                     const int q = q0 + qt * 32 + 8 * gq + 4 * half + e;
                     float p = exp2f(fmaf(sc[v], sl2, -l4[e]));
-                    if ((CAUSAL && key > q) || key >= klimit) p = 0.f;
+                    if ((CAUSAL && key > q) || key_dead) p = 0.f;
                     sc[v] = p;
-                    dp[v] = (p * scale) * (dp[v] - d4[e]);
+                    dp[v] = p * (dp[v] - d4[e]);         // the factor `scale` of dS is applied to dK at the end
                 }
             }
 #pragma unroll
@@ -373,7 +374,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16* __restri
         }
     }
     bf16* out = dqkv + ((long)b * s + key) * ld + (long)h * DH;
-    store_headrow<DT>(out + D, dk, half, 1.0f);
+    store_headrow<DT>(out + D, dk, half, scale);
     store_headrow<DT>(out + 2 * D, dv, half, 1.0f);
 }
 
@@ -444,8 +445,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             for (int v = 0; v < 16; ++v) {
                 const int key = k0 + kt * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
                 float p = exp2f(fmaf(sc[v], sl2, -lse_q));
-                if ((CAUSAL && key > q) || key >= klimit) p = 0.f;
-                dp[v] = (p * scale) * (dp[v] - delta_q);
+                if ((CAUSAL && key > q) || (!CAUSAL && key >= klimit)) p = 0.f;   // causal stages carry no padding mask
+                dp[v] = p * (dp[v] - delta_q);           // the factor `scale` of dS is applied to dQ at the end
             }
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
@@ -456,7 +457,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             }
         }
     }
-    store_headrow<DT>(dqkv + ((long)b * s + q) * ld + (long)h * DH, dq, half, 1.0f);
+    store_headrow<DT>(dqkv + ((long)b * s + q) * ld + (long)h * DH, dq, half, scale);
 }
 
 }  // namespace amdp

@@ -468,6 +468,7 @@ int flash_fwd_launch(amdp_stage* st, const void* qkv, void* o, float* lse2, cons
     const Dims& d = st->d;
     const float sc = LOG2E / sqrtf((float)d.dh);
     const int Dk = d.H * dhk;
+    if (d.causal && valid) return AMDP_E_INVAL;      // the causal kernels carry no padding mask
     dim3 grid((d.s / 128) * d.b * d.H);
     ProfScope ps(st, "flash_attention_fwd", 4.0 * d.b * d.H * (double)d.s * d.s * d.dh * (d.causal ? (d.s + 1.0) / (2.0 * d.s) : 1.0), 0.0);
 #define FLASH_FWD(DH, C) hipLaunchKernelGGL((flash_fwd_kernel<DH, C>), grid, dim3(256), 0, st->launch, (const bf16*)qkv, \
@@ -496,6 +497,7 @@ int flash_bwd_launch(amdp_stage* st, const void* dO, const void* qkv, const void
     const Dims& d = st->d;
     const float scale = 1.0f / sqrtf((float)d.dh);
     const int Dk = d.H * dhk;
+    if (d.causal && valid) return AMDP_E_INVAL;      // the causal kernels carry no padding mask
     const double unit = 2.0 * d.b * d.H * (double)d.s * d.s * d.dh * (d.causal ? (d.s + 1.0) / (2.0 * d.s) : 1.0);
     dim3 grid((d.s / 128) * d.b * d.H);
     {
