@@ -129,6 +129,56 @@ int amdp_schedule_stats(const amdp_event_t* events, size_t n, int32_t threshold,
 int amdp_stage_map(int32_t depth, int32_t pipeline, int32_t stage, int32_t* gpu_out);
 
 /* ------------------------------------------------------------------------
+ * Timed simulation of the whole multi-directional system (Section 3.2): d GPUs,
+ * P <= d/2 pipelines placed by amdp_stage_map, each running `minibatches`
+ * minibatches; stage 0 of a pipeline keeps at most inject_limit + preload
+ * minibatches in flight; forward(i,m) precedes forward(i+1,m) and
+ * backward(i,m), backward(i,m) precedes backward(i-1,m) (Appendix B.4). A GPU
+ * runs one operation at a time without preemption and, when free, starts the
+ * ready operation that became ready first (the FIFO rule of Section 3.2); ties
+ * go to a backward before a forward, then the lower pipeline, then the lower
+ * minibatch. Time is in integer units: every forward takes t_forward, every
+ * backward t_backward, transfers take none. Host only, integer only.
+ * The paper's statements this reproduces: one pipeline keeps a GPU busy n/d of
+ * the time; with P = d/2 and preload = floor(t_backward / t_forward) the
+ * bubbles all but vanish.
+ * ------------------------------------------------------------------------ */
+typedef struct amdp_sim_params_t {
+    uint32_t struct_size;
+    int32_t depth;          /* d >= 1: stages per pipeline = number of GPUs */
+    int32_t pipelines;      /* 1 <= P <= max(1, d/2) */
+    int32_t inject_limit;   /* n >= 1 */
+    int32_t preload;        /* extra minibatches stage 0 may have in flight, >= 0 */
+    int32_t minibatches;    /* per pipeline, >= 0 */
+    int32_t t_forward;      /* >= 1 */
+    int32_t t_backward;     /* >= 1 */
+} amdp_sim_params_t;
+
+typedef struct amdp_sim_op_t {
+    uint8_t  kind;       /* AMDP_EV_F or AMDP_EV_B */
+    uint8_t  pipeline;
+    uint16_t stage;
+    int32_t  mb;         /* minibatch index inside its pipeline */
+    int32_t  gpu;
+    int64_t  start, end;
+} amdp_sim_op_t;
+
+typedef struct amdp_sim_result_t {
+    uint32_t struct_size;
+    int32_t  max_inflight;   /* most minibatches one pipeline had in flight at stage 0 */
+    int64_t  makespan;       /* end of the last operation */
+    int64_t  busy_total;     /* sum over GPUs of the time spent in operations */
+    int64_t  busy_min, busy_max;   /* over GPUs */
+} amdp_sim_result_t;
+
+/* Writes the 2*d*P*minibatches operations in order of start time (ties: lower
+ * GPU first) to `ops` (host; may be NULL with cap = 0 to size: *n_ops is always
+ * set, AMDP_E_CAPACITY if cap is too small, in which case only `result` is
+ * filled). gpu_busy (host, [depth], may be NULL) receives each GPU's busy time. */
+int amdp_system_simulate(const amdp_sim_params_t* params, amdp_sim_op_t* ops, size_t cap, size_t* n_ops,
+                         int64_t* gpu_busy, amdp_sim_result_t* result);
+
+/* ------------------------------------------------------------------------
  * Stage
  * ------------------------------------------------------------------------ */
 

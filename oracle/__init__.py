@@ -4,6 +4,7 @@ TEST INFRASTRUCTURE ONLY. This package is the plain, slow, obviously-correct
 definition of what the stage computes, written from the paper (AMDP:
 Asynchronous Multi-Directional Pipeline Parallelism): the per-stage schedule
 with version tags (Sections 3.1-3.3, Lemma 1 / Lemma B.1, Appendix B.4), the
+timed whole-system simulation of Section 3.2 (stage map, FIFO conflicts), the
 forward and backward pass of a slice of GPT/BERT transformer blocks (Section
 4.1, Table 2), gradient accumulation over a window (Section 3.3) and the Adam
 update (Appendix B.1). It shares no code with the HIP library and is imported
@@ -23,6 +24,10 @@ Pins (see tests, all runnable without a GPU):
   accumulate          sum-of-per-minibatch-gradients invariant.
   adam                closed form of the first step; torch.optim.Adam fp64;
                       the bias-correction-free form printed in Appendix B.1.
+  system.simulate     serial closed form (one minibatch in flight), the active
+                      ratio n/d and the no-bubble statement of Section 3.2, the
+                      causal constraints of Appendix B.4 on random cases, a
+                      clock-tick re-simulation on tiny cases.
   bf16 rounding       exhaustive comparison with torch's bfloat16 cast on a
                       sweep of bit patterns.
 """

@@ -45,6 +45,22 @@ class amdp_sched_stats_t(C.Structure):
                 ("max_affected_per_window", C.c_int32), ("max_live_versions", C.c_int32)]
 
 
+class amdp_sim_params_t(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("depth", C.c_int32), ("pipelines", C.c_int32),
+                ("inject_limit", C.c_int32), ("preload", C.c_int32), ("minibatches", C.c_int32),
+                ("t_forward", C.c_int32), ("t_backward", C.c_int32)]
+
+
+class amdp_sim_op_t(C.Structure):
+    _fields_ = [("kind", C.c_uint8), ("pipeline", C.c_uint8), ("stage", C.c_uint16), ("mb", C.c_int32),
+                ("gpu", C.c_int32), ("start", C.c_int64), ("end", C.c_int64)]
+
+
+class amdp_sim_result_t(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("max_inflight", C.c_int32), ("makespan", C.c_int64),
+                ("busy_total", C.c_int64), ("busy_min", C.c_int64), ("busy_max", C.c_int64)]
+
+
 class amdp_stage_config_t(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("block_kind", C.c_int32), ("n_layers", C.c_int32),
                 ("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ffn", C.c_int32),
@@ -116,6 +132,8 @@ def lib():
         "amdp_schedule_generate": (C.c_int, [P(amdp_sched_params_t), P(amdp_event_t), sz, P(sz)]),
         "amdp_schedule_stats": (C.c_int, [P(amdp_event_t), sz, i32, P(amdp_sched_stats_t)]),
         "amdp_stage_map": (C.c_int, [i32, i32, i32, P(i32)]),
+        "amdp_system_simulate": (C.c_int, [P(amdp_sim_params_t), P(amdp_sim_op_t), sz, P(sz), P(C.c_int64),
+                                           P(amdp_sim_result_t)]),
         "amdp_stage_n_params": (sz, [P(amdp_stage_config_t)]),
         "amdp_stage_workspace_bytes": (sz, [P(amdp_stage_config_t)]),
         "amdp_stage_param_layout": (C.c_int, [P(amdp_stage_config_t), P(amdp_param_desc_t), i32, P(i32)]),
@@ -143,6 +161,7 @@ def lib():
 
 
 EXPORTED = ["amdp_strerror", "amdp_last_hip_error", "amdp_schedule_generate", "amdp_schedule_stats", "amdp_stage_map",
+            "amdp_system_simulate",
             "amdp_stage_n_params", "amdp_stage_workspace_bytes", "amdp_stage_param_layout",
             "amdp_stage_create", "amdp_stage_destroy", "amdp_stage_set_state", "amdp_stage_get_state",
             "amdp_stage_get_staged_grad", "amdp_stage_resident_versions", "amdp_stage_forward",
@@ -183,6 +202,24 @@ def amdp_stage_map(depth, pipeline, stage):
     g = C.c_int32(-1)
     _check(lib().amdp_stage_map(depth, pipeline, stage, C.byref(g)), "amdp_stage_map")
     return g.value
+
+
+def amdp_system_simulate(depth, pipelines, minibatches, t_forward=1, t_backward=2, inject_limit=2, preload=0):
+    """Returns (ops, info): ops = list of (kind, pipeline, stage, mb, gpu, start, end) in start order."""
+    p = amdp_sim_params_t(C.sizeof(amdp_sim_params_t), depth, pipelines, inject_limit, preload, minibatches,
+                          t_forward, t_backward)
+    res = amdp_sim_result_t(C.sizeof(amdp_sim_result_t))
+    n = C.c_size_t(0)
+    rc = lib().amdp_system_simulate(C.byref(p), None, 0, C.byref(n), None, C.byref(res))
+    if rc not in (0, E_CAPACITY):
+        raise AmdpError(rc, "amdp_system_simulate")
+    arr = (amdp_sim_op_t * max(1, n.value))()
+    busy = (C.c_int64 * depth)()
+    _check(lib().amdp_system_simulate(C.byref(p), arr, n.value, C.byref(n), busy, C.byref(res)),
+           "amdp_system_simulate")
+    ops = [(o.kind, o.pipeline, o.stage, o.mb, o.gpu, o.start, o.end) for o in arr[:n.value]]
+    return ops, dict(makespan=res.makespan, busy=list(busy), max_inflight=res.max_inflight,
+                     busy_total=res.busy_total, busy_min=res.busy_min, busy_max=res.busy_max)
 
 
 def make_config(block_kind, n_layers, d_model, n_heads, d_ffn, seq_len, microbatch, dtype,

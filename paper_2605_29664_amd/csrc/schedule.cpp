@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cstring>
 #include <map>
+#include <queue>
 #include <vector>
 
 namespace {
@@ -158,6 +159,126 @@ extern "C" int amdp_stage_map(int32_t depth, int32_t pipeline, int32_t stage, in
     const int d = depth, j = pipeline, i = stage;
     int g = (j % 2 == 0) ? (2 * j + i) % d : (2 * j - i + d + 1) % d;
     *gpu_out = ((g % d) + d) % d;
+    return AMDP_OK;
+}
+
+namespace {
+
+inline int map_gpu(int d, int j, int i) {
+    const int g = (j % 2 == 0) ? (2 * j + i) % d : (2 * j - i + d + 1) % d;
+    return ((g % d) + d) % d;
+}
+
+// A ready operation; ordering = the FIFO rule with its tie-breaks.
+struct ReadyOp {
+    int64_t ready;
+    int kind, pipeline, mb, stage;
+    bool operator>(const ReadyOp& o) const {
+        if (ready != o.ready) return ready > o.ready;
+        if (kind != o.kind) return kind < o.kind;            // backward (1) before forward (0)
+        if (pipeline != o.pipeline) return pipeline > o.pipeline;
+        if (mb != o.mb) return mb > o.mb;
+        return stage > o.stage;
+    }
+};
+
+}  // namespace
+
+extern "C" int amdp_system_simulate(const amdp_sim_params_t* p, amdp_sim_op_t* ops, size_t cap, size_t* n_ops,
+                                    int64_t* gpu_busy, amdp_sim_result_t* res) {
+    if (!p || !n_ops || !res || p->struct_size != sizeof(amdp_sim_params_t) ||
+        res->struct_size != sizeof(amdp_sim_result_t))
+        return AMDP_E_INVAL;
+    const int d = p->depth, P = p->pipelines, M = p->minibatches, tF = p->t_forward, tB = p->t_backward;
+    if (d < 1 || d > 65535 || P < 1 || P > std::max(1, d / 2) || P > 255 || M < 0 || tF < 1 || tB < 1 ||
+        p->inject_limit < 1 || p->preload < 0)
+        return AMDP_E_INVAL;
+    const long long limit = (long long)p->inject_limit + p->preload;
+    const size_t total = 2 * (size_t)d * P * M;
+    *n_ops = total;
+    const bool record = ops && total <= cap;
+
+    typedef std::priority_queue<ReadyOp, std::vector<ReadyOp>, std::greater<ReadyOp>> Queue;
+    std::vector<Queue> ready((size_t)d);
+    struct Running { bool on = false; int kind, pipeline, stage, mb; int64_t start, end; };
+    std::vector<Running> running((size_t)d);
+    std::vector<int64_t> busy((size_t)d, 0);
+    std::vector<int> inflight((size_t)P, 0), next_inject((size_t)P, 0);
+    std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>> ends;
+    std::vector<amdp_sim_op_t> done;
+    if (record) done.reserve(total);
+    int max_inflight = 0;
+    int64_t makespan = 0;
+
+    auto make_ready = [&](int64_t t, int kind, int j, int m, int i) {
+        ready[(size_t)map_gpu(d, j, i)].push(ReadyOp{t, kind, j, m, i});
+    };
+    for (int j = 0; j < P; ++j) {
+        const int first = (int)std::min<long long>(limit, M);
+        for (int m = 0; m < first; ++m) make_ready(0, AMDP_EV_F, j, m, 0);
+        inflight[j] = next_inject[j] = first;
+        max_inflight = std::max(max_inflight, first);
+    }
+    int64_t t = 0;
+    for (;;) {
+        for (int g = 0; g < d; ++g) {          // start what can start now
+            if (running[g].on || ready[g].empty() || ready[g].top().ready > t) continue;
+            const ReadyOp r = ready[g].top();
+            ready[g].pop();
+            const int dur = r.kind == AMDP_EV_F ? tF : tB;
+            running[g] = Running{true, r.kind, r.pipeline, r.stage, r.mb, t, t + dur};
+            busy[g] += dur;
+            ends.push(t + dur);
+        }
+        if (ends.empty()) break;
+        t = ends.top();
+        while (!ends.empty() && ends.top() == t) ends.pop();
+        for (int g = 0; g < d; ++g) {          // finish what ends now
+            Running& r = running[g];
+            if (!r.on || r.end != t) continue;
+            r.on = false;
+            makespan = std::max(makespan, r.end);
+            if (record) {
+                amdp_sim_op_t o;
+                std::memset(&o, 0, sizeof(o));
+                o.kind = (uint8_t)r.kind; o.pipeline = (uint8_t)r.pipeline; o.stage = (uint16_t)r.stage;
+                o.mb = r.mb; o.gpu = g; o.start = r.start; o.end = r.end;
+                done.push_back(o);
+            }
+            const int j = r.pipeline, i = r.stage, m = r.mb;
+            if (r.kind == AMDP_EV_F) {
+                if (i + 1 < d) make_ready(t, AMDP_EV_F, j, m, i + 1);
+                else make_ready(t, AMDP_EV_B, j, m, i);
+            } else if (i > 0) {
+                make_ready(t, AMDP_EV_B, j, m, i - 1);
+            } else {
+                --inflight[j];
+                if (next_inject[j] < M) {
+                    make_ready(t, AMDP_EV_F, j, next_inject[j]++, 0);
+                    max_inflight = std::max(max_inflight, ++inflight[j]);
+                }
+            }
+        }
+    }
+    res->max_inflight = max_inflight;
+    res->makespan = makespan;
+    res->busy_total = 0;
+    res->busy_min = d ? busy[0] : 0;
+    res->busy_max = 0;
+    for (int g = 0; g < d; ++g) {
+        res->busy_total += busy[g];
+        res->busy_min = std::min(res->busy_min, busy[g]);
+        res->busy_max = std::max(res->busy_max, busy[g]);
+        if (gpu_busy) gpu_busy[g] = busy[g];
+    }
+    if (ops && total > cap) return AMDP_E_CAPACITY;
+    if (!ops && total) return AMDP_E_CAPACITY;
+    if (record) {
+        std::stable_sort(done.begin(), done.end(), [](const amdp_sim_op_t& a, const amdp_sim_op_t& b) {
+            return a.start != b.start ? a.start < b.start : a.gpu < b.gpu;
+        });
+        std::copy(done.begin(), done.end(), ops);
+    }
     return AMDP_OK;
 }
 

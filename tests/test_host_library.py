@@ -163,3 +163,31 @@ def test_generate_rejects_bad_parameters_and_sizes_output():
     assert amdp.lib().amdp_schedule_generate(C.byref(p), small, 3, C.byref(n)) == amdp.E_CAPACITY
     assert n.value == 3 * 8 + 2
     assert amdp.amdp_strerror(amdp.E_STASH_FULL).startswith("no free weight-version slot")
+
+
+def test_system_simulation_equals_oracle():
+    """The library's timed whole-system simulation reproduces the oracle's
+    timeline operation by operation (integer work: exact)."""
+    import random
+    from oracle import system as OS
+    rng = random.Random(2966)
+    cases = [(4, 2, 6, 1, 2, 2, 0), (8, 4, 20, 1, 2, 2, 2), (16, 8, 5, 2, 3, 2, 1), (1, 1, 3, 1, 1, 1, 0), (6, 3, 0, 1, 2, 2, 0)]
+    for _ in range(40):
+        d = rng.randint(1, 10)
+        cases.append((d, rng.randint(1, max(1, d // 2)), rng.randint(0, 9), rng.randint(1, 4), rng.randint(1, 7),
+                      rng.randint(1, 3), rng.randint(0, 3)))
+    for d, P, M, tF, tB, n, pre in cases:
+        ops, info = amdp.amdp_system_simulate(d, P, M, tF, tB, n, pre)
+        ref_ops, ref = OS.simulate(d, P, M, tF, tB, inject_limit=n, preload=pre)
+        assert ops == [tuple(o) for o in ref_ops], (d, P, M, tF, tB, n, pre)
+        assert info["makespan"] == ref["makespan"] and info["busy"] == ref["busy"]
+        assert info["max_inflight"] == ref["max_inflight"]
+        assert info["busy_total"] == sum(ref["busy"]) and info["busy_min"] == min(ref["busy"])
+        assert info["busy_max"] == max(ref["busy"])
+
+
+def test_system_simulation_rejects_bad_parameters():
+    for bad in [(0, 1, 1, 1, 1, 2, 0), (4, 3, 1, 1, 1, 2, 0), (4, 2, -1, 1, 1, 2, 0), (4, 2, 1, 0, 1, 2, 0),
+                (4, 2, 1, 1, 0, 2, 0), (4, 2, 1, 1, 1, 0, 0), (4, 2, 1, 1, 1, 2, -1)]:
+        with pytest.raises(amdp.AmdpError):
+            amdp.amdp_system_simulate(*bad)
