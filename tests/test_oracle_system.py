@@ -171,3 +171,14 @@ def test_conflicting_backwards_are_served_in_order_of_arrival():
                 assert (ready_time[a], -a.kind) <= (ready_time[b], -b.kind)
                 waited += 1
     assert waited > 0          # the case does contain conflicts
+
+
+@pytest.mark.parametrize("d,n,tF,tB", [(4, 4, 1, 2), (8, 8, 1, 2), (6, 3, 1, 2), (8, 5, 2, 3), (2, 2, 1, 1)])
+def test_one_flushed_minibatch_has_the_bubble_ratio_of_table_1(d, n, tF, tB):
+    """One pipeline, one minibatch of n <= d microbatches all admitted at once
+    and then drained: the classic synchronous schedule, whose bubble ratio
+    Table 1 prints as (d-1)/(n+d-1)."""
+    _, info = S.simulate(d, 1, n, tF, tB, inject_limit=d)
+    assert info["makespan"] == (n + d - 1) * (tF + tB)
+    bubble = 1 - sum(info["busy"]) / (d * info["makespan"])
+    assert abs(bubble - (d - 1) / (n + d - 1)) < 1e-12
