@@ -65,6 +65,35 @@ __device__ __forceinline__ void epilogue_store(const Epilogue& e, void* C, long 
     if (e.aux_out) ((T*)e.aux_out)[m * ldc + n] = from_f32<T>(gelu_f(v));
 }
 
+// Cheaper GELU terms for the bf16 epilogues, where they are a visible share of
+// a launch (the d/du GELU epilogue of configuration 2's FFN1 backward carried 12
+// other vector instructions per matrix instruction with erff): erf from the
+// five-term rational-exponential form of Abramowitz & Stegun 7.1.26 (absolute
+// error below 1.5e-7, a bf16 result keeps 8 bits), sharing its exp(-u^2/2) with
+// the density. cdf = Phi(u), pdf = phi(u).
+__device__ __forceinline__ void gelu_terms_fast(float u, float& cdf, float& pdf) {
+    const float x = fabsf(u) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+    const float e = __builtin_amdgcn_exp2f(-0.72134752044448170f * u * u);    // exp(-u*u/2)
+    float p = fmaf(1.061405429f, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    const float erf_abs = fmaf(-p * t, e, 1.0f);                             // erf(|u|/sqrt 2)
+    cdf = fmaf(0.5f, copysignf(erf_abs, u), 0.5f);
+    pdf = 0.39894228040143268f * e;
+}
+__device__ __forceinline__ float gelu_fast(float u) {
+    float cdf, pdf;
+    gelu_terms_fast(u, cdf, pdf);
+    return u * cdf;
+}
+__device__ __forceinline__ float gelu_grad_fast(float u) {
+    float cdf, pdf;
+    gelu_terms_fast(u, cdf, pdf);
+    return fmaf(u, pdf, cdf);
+}
+
 // Same epilogue for 8 consecutive columns n..n+7 of row m (bf16 stage dtype);
 // every pointer involved is 16-byte aligned at these columns.
 __device__ __forceinline__ void epilogue_store8(const Epilogue& e, void* C, long ldc, long m, long n,
@@ -79,7 +108,7 @@ __device__ __forceinline__ void epilogue_store8(const Epilogue& e, void* C, long
     if (e.gelu_u) {
         const bf16x8 u = *(const bf16x8*)((const bf16*)e.gelu_u + m * e.ldu + n);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] *= gelu_grad_f((float)u[k]);
+        for (int k = 0; k < 8; ++k) v[k] *= gelu_grad_fast((float)u[k]);
     }
     if (e.res) {
         const bf16x8 r = *(const bf16x8*)((const bf16*)e.res + m * e.ldr + n);
@@ -100,7 +129,7 @@ __device__ __forceinline__ void epilogue_store8(const Epilogue& e, void* C, long
     if (e.aux_out) {
         bf16x8 o;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) o[k] = (bf16)gelu_f(v[k]);
+        for (int k = 0; k < 8; ++k) o[k] = (bf16)gelu_fast(v[k]);
         *(bf16x8*)((bf16*)e.aux_out + m * ldc + n) = o;
     }
 }
