@@ -61,6 +61,9 @@ def main():
     ap.add_argument("--config", type=str, default="2", help="benchmark configuration 1..5 or a test shape name")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--fused-accumulate", action="store_true",
+                    help="backward adds parameter gradients straight into the sum (amdp_stage_set_fused_accumulate); "
+                         "default is the schedule's own order with the accumulation as its own kernel")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus must be 1 "
@@ -79,7 +82,7 @@ def main():
     T, P = w.threshold, w.pipelines
     K, Wu = args.steps, args.warmup
     inflight = w.act_slots
-    M = (Wu + K + 3) * T + inflight
+    M = (Wu + 2 * K + 3) * T + inflight      # warm-up, timed, 2 profiled, timed again with fused accumulation
 
     cfg = make_cfg(w)
     stage = amdp.Stage(cfg, device="cuda:0")
@@ -87,6 +90,8 @@ def main():
     theta0 = torch.from_numpy(W.make_theta(w, layout)).to(dev)
     stage.amdp_stage_set_state(theta0)
     del theta0
+    if args.fused_accumulate:
+        stage.amdp_stage_set_fused_accumulate(True)
 
     ring = max(2, 2 * inflight)
     dt = stage.act_dtype
@@ -150,7 +155,8 @@ def main():
                    "layers": w.n_layers, "d_model": w.d_model, "heads": w.n_heads, "d_ffn": w.d_ffn,
                    "seq_len": w.seq_len, "microbatch": w.microbatch, "vocab": w.vocab if w.has_lm_head else 0,
                    "depth": w.depth, "pipelines": P, "stage": w.stage, "minibatches_per_update": T,
-                   "tokens_per_step": T * w.tokens, "parallelism": "1 stage on 1 GPU"},
+                   "tokens_per_step": T * w.tokens, "parallelism": "1 stage on 1 GPU",
+                   "accumulation": "fused into backward" if args.fused_accumulate else "own kernel per minibatch"},
         "end_to_end_mfu": flops_step * K / elapsed / (peak * 1e12),
         "algorithmic_tflop_per_step": flops_step / 1e12,
     }
@@ -217,6 +223,21 @@ def main():
                                               **({"gbs": round(r["bytes"] / r["ms"] / 1e6, 1)} if r["bytes"] > 0 else {})}
                                           for n, r in sorted(iso.items(), key=lambda kv: -kv[1]["ms"]) if r["ms"] > 0}
 
+    # ---- the same steps with the accumulation fused into backward (an option of
+    # the library; `value` above is the schedule's own order) --------------------
+    if not args.fused_accumulate and len(steps) >= n_warm + 2 * K + 2:
+        stage.amdp_stage_set_fused_accumulate(True)
+        first = n_warm + K + 2
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(first, first + K):
+            run_step(steps[i])
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        result["fused_accumulate"] = {"value": tokens / el, "unit": "tokens/s", "ms_per_step": 1e3 * el / K,
+                                      "note": "amdp_stage_set_fused_accumulate(1): dW products and column sums add "
+                                              "into the gradient sum directly; bit-identical state, no per-minibatch gradient"}
+
     stage.close()
     del stage
     torch.cuda.empty_cache()
@@ -229,8 +250,8 @@ def main():
 
 
 def cpu_baseline(w):
-    """Times the oracle as it stands: forward + backward + accumulate of ONE
-    minibatch plus one Adam step over the stage's parameters (charged 1/T per
+    """Times the oracle as it stands: forward + backward + accumulate of a few
+    whole minibatches plus one Adam step over the stage's parameters (charged 1/T per
     minibatch), in fp64, on the host's cores."""
     import numpy as np
     import workloads as W
@@ -243,20 +264,23 @@ def cpu_baseline(w):
         threads = os.cpu_count()
     ost = OStage.from_workload(w)
     theta = W.make_theta(w, ost.layout).astype(np.float64)
-    x = W.make_x(w, 0)
-    aux = W.make_targets(w, 0) if w.has_lm_head else (W.make_valid_len(w, 0) if w.block_kind == 1 else None)
-    dy = None if w.has_lm_head else W.make_dy(w, 0)
-    t0 = time.perf_counter()
-    _, saved = ost.forward(theta, x, aux)
-    _, g = ost.backward(theta, saved, dy)
+    # whole minibatches until about 12 s of CPU time are spent (at least one, at most four)
     G = np.zeros_like(theta)
-    optim.accumulate(G, g)
+    n_mb, t0 = 0, time.perf_counter()
+    while n_mb < 4 and (n_mb == 0 or time.perf_counter() - t0 < 12.0):
+        x = W.make_x(w, n_mb)
+        aux = W.make_targets(w, n_mb) if w.has_lm_head else (W.make_valid_len(w, n_mb) if w.block_kind == 1 else None)
+        dy = None if w.has_lm_head else W.make_dy(w, n_mb)
+        _, saved = ost.forward(theta, x, aux)
+        _, g = ost.backward(theta, saved, dy)
+        optim.accumulate(G, g)
+        n_mb += 1
     t1 = time.perf_counter()
     optim.adam_step(theta, np.zeros_like(theta), np.zeros_like(theta), G, 1, w.lr, w.beta1, w.beta2, w.eps)
     t2 = time.perf_counter()
-    per_mb = (t1 - t0) + (t2 - t1) / w.threshold
+    per_mb = (t1 - t0) / n_mb + (t2 - t1) / w.threshold
     return {"value": w.tokens / per_mb, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"1 minibatch ({w.tokens} tokens) forward+backward+accumulate in fp64 numpy "
+            "sample": f"{n_mb} minibatch(es) of {w.tokens} tokens forward+backward+accumulate in fp64 numpy "
                       f"({t1 - t0:.1f} s) + 1/{w.threshold} of one Adam step ({t2 - t1:.2f} s)",
             "host_cpus": os.cpu_count()}
 

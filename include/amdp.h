@@ -310,6 +310,17 @@ int amdp_apply_update(amdp_stage_t* stage, const amdp_adam_t* hp, uint32_t* new_
  * isolation); default is on. Results are bit-identical either way. */
 int amdp_stage_set_overlap(amdp_stage_t* stage, int32_t on);
 
+/* on = 1: backward adds the minibatch's parameter gradients straight into the
+ * sum G (the dW products and the column sums end in G += instead of g =), and
+ * amdp_grad_accumulate only does its bookkeeping. The sum is bit-identical to
+ * the two-step form (same fp32 additions in the same order) and 12 bytes per
+ * parameter per minibatch of HBM traffic disappear; the price is that the
+ * minibatch's own gradient is never materialised (amdp_stage_get_staged_grad
+ * returns AMDP_E_MB_STATE). Default 0: the accumulation is its own kernel, as
+ * the schedule's A event has it. AMDP_E_MB_STATE between a backward and its
+ * accumulate. */
+int amdp_stage_set_fused_accumulate(amdp_stage_t* stage, int32_t on);
+
 /* Orders everything the stage has enqueued on its own side stream (at most the
  * accumulations since the last join) before whatever the caller enqueues next
  * on its stream. Needed only by a caller that wants a point where the stage's

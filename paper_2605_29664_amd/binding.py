@@ -149,6 +149,7 @@ def lib():
         "amdp_apply_update": (C.c_int, [vp, P(amdp_adam_t), P(u32)]),
         "amdp_stage_set_overlap": (C.c_int, [vp, i32]),
         "amdp_stage_join": (C.c_int, [vp]),
+        "amdp_stage_set_fused_accumulate": (C.c_int, [vp, i32]),
         "amdp_stage_profile_begin": (C.c_int, [vp]),
         "amdp_stage_profile_end": (C.c_int, [vp, P(amdp_profile_entry_t), i32, P(i32)]),
     }
@@ -166,7 +167,8 @@ EXPORTED = ["amdp_strerror", "amdp_last_hip_error", "amdp_schedule_generate", "a
             "amdp_stage_create", "amdp_stage_destroy", "amdp_stage_set_state", "amdp_stage_get_state",
             "amdp_stage_get_staged_grad", "amdp_stage_resident_versions", "amdp_stage_forward",
             "amdp_stage_backward", "amdp_grad_accumulate", "amdp_apply_update",
-            "amdp_stage_set_overlap", "amdp_stage_join", "amdp_stage_profile_begin", "amdp_stage_profile_end"]
+            "amdp_stage_set_overlap", "amdp_stage_join", "amdp_stage_set_fused_accumulate",
+            "amdp_stage_profile_begin", "amdp_stage_profile_end"]
 
 
 def _check(rc, what):
@@ -356,6 +358,9 @@ class Stage:
         nv = C.c_uint32(0)
         _check(lib().amdp_apply_update(self.handle, C.byref(hp), C.byref(nv)), "amdp_apply_update")
         return nv.value
+
+    def amdp_stage_set_fused_accumulate(self, on):
+        _check(lib().amdp_stage_set_fused_accumulate(self.handle, int(bool(on))), "amdp_stage_set_fused_accumulate")
 
     def amdp_stage_join(self):
         _check(lib().amdp_stage_join(self.handle), "amdp_stage_join")

@@ -51,6 +51,7 @@ struct Epilogue {
     long ldr = 0, ldu = 0;
     float alpha = 1.0f;
     int out_f32 = 0;                // C is float instead of the stage dtype
+    int accumulate = 0;             // with out_f32: C[m,n] += v instead of C[m,n] = v
 };
 
 template <class T>
@@ -60,7 +61,10 @@ __device__ __forceinline__ void epilogue_store(const Epilogue& e, void* C, long 
     if (e.bias) v += to_f32(((const T*)e.bias)[n]);
     if (e.gelu_u) v *= gelu_grad_f(to_f32(((const T*)e.gelu_u)[m * e.ldu + n]));
     if (e.res) v += to_f32(((const T*)e.res)[m * e.ldr + n]);
-    if (e.out_f32) ((float*)C)[m * ldc + n] = v;
+    if (e.out_f32) {
+        float* p = (float*)C + m * ldc + n;
+        *p = e.accumulate ? *p + v : v;
+    }
     else ((T*)C)[m * ldc + n] = from_f32<T>(v);
     if (e.aux_out) ((T*)e.aux_out)[m * ldc + n] = from_f32<T>(gelu_f(v));
 }
@@ -118,6 +122,10 @@ __device__ __forceinline__ void epilogue_store8(const Epilogue& e, void* C, long
     if (e.out_f32) {
         float* p = (float*)C + m * ldc + n;
         f32x4 lo = {v[0], v[1], v[2], v[3]}, hi = {v[4], v[5], v[6], v[7]};
+        if (e.accumulate) {
+            lo += *(const f32x4*)p;
+            hi += *(const f32x4*)(p + 4);
+        }
         *(f32x4*)p = lo;
         *(f32x4*)(p + 4) = hi;
     } else {

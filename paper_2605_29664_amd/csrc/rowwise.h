@@ -185,8 +185,10 @@ __global__ __launch_bounds__(256) void colreduce_partial_kernel(const T* __restr
 }
 // Stage 2: out[c] = sum over chunks. A block owns 64 columns; its 4 groups of
 // 64 threads each sum every 4th chunk, then the groups are added in fixed order.
+// accumulate != 0: out[c] += that sum.
 __global__ __launch_bounds__(256) void colreduce_final_kernel(const float* __restrict__ partial,
-                                                             float* __restrict__ out, int width, int chunks) {
+                                                             float* __restrict__ out, int width, int chunks,
+                                                             int accumulate) {
     __shared__ float red[4][64];
     const int j = threadIdx.x & 63, grp = threadIdx.x >> 6;
     const int c = blockIdx.x * 64 + j;
@@ -195,7 +197,10 @@ __global__ __launch_bounds__(256) void colreduce_final_kernel(const float* __res
         for (int k = grp; k < chunks; k += 4) s += partial[(long)k * width + c];
     red[grp][j] = s;
     __syncthreads();
-    if (grp == 0 && c < width) out[c] = (red[0][j] + red[1][j]) + (red[2][j] + red[3][j]);
+    if (grp == 0 && c < width) {
+        const float t = (red[0][j] + red[1][j]) + (red[2][j] + red[3][j]);
+        out[c] = accumulate ? out[c] + t : t;
+    }
 }
 
 // -------------------------------------------------------------------- softmax

@@ -229,6 +229,7 @@ struct amdp_stage {
     hipEvent_t events[16] = {};
     int ev_next = 0;
     bool overlap = true;
+    bool fused_acc = false;        // backward adds parameter gradients into G directly
     int flash = 1;          // fused attention: 1 on (default), 0 off, 2 test mode: run after the three-kernel path
     hipEvent_t next_event() { ev_next = (ev_next + 1) % 16; return events[ev_next]; }
 
@@ -428,7 +429,7 @@ int colreduce(amdp_stage* st, const void* dy, const void* x, const float* stats,
     TRY(after_launch());
     const int width = LN ? 2 * C : C;
     hipLaunchKernelGGL(colreduce_final_kernel, dim3((width + 63) / 64), dim3(256), 0, st->launch, partial,
-                       out, width, chunks);
+                       out, width, chunks, st->fused_acc ? 1 : 0);
     return after_launch();
 }
 
@@ -660,6 +661,7 @@ int linear_dw(amdp_stage* st, const void* X, const void* dY, float* dW, int M, i
     GemmArgs g{};
     g.A = X; g.B = dY; g.C = dW; g.M = K; g.N = N; g.K = M; g.ldc = N;
     g.epi.out_f32 = 1;
+    g.epi.accumulate = st->fused_acc ? 1 : 0;
     return gemm(st, G_TN, g, K, N);
 }
 
@@ -748,7 +750,8 @@ int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, co
     const Dims& d = st->d;
     const T* W = (const T*)st->version_ptr(vslot);
     char* S = st->act_ptr(aslot);
-    float* g = st->at<float>(st->w.g);
+    // parameter gradients go to the staging buffer, or straight into the sum
+    float* g = st->at<float>(st->fused_acc ? st->w.G : st->w.g);
     void* dO = st->at<>(st->w.dO);      // main chain only
     void* dP = st->at<>(st->w.dP);      // main chain only
 
@@ -761,6 +764,7 @@ int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, co
             GemmArgs a{};
             a.A = S + sl.dlogits; a.B = S + sl.z; a.C = g + d.off_embed();
             a.M = (int)d.Vld; a.N = d.D; a.K = d.N; a.ldc = d.D; a.epi.out_f32 = 1;
+            a.epi.accumulate = st->fused_acc ? 1 : 0;
             TRY(gemm(st, G_TN, a, d.Vld, d.D));
         });
         {   // dz = dlogits E
@@ -987,6 +991,7 @@ extern "C" int amdp_stage_get_staged_grad(amdp_stage_t* st, float* g) {
     if (!st || !g) return AMDP_E_INVAL;
     if (st->staged_slot < 0) return AMDP_E_MB_STATE;
     if ((uintptr_t)g % 4) return AMDP_E_INVAL;
+    if (st->fused_acc) return AMDP_E_MB_STATE;           // the gradient went straight into the sum
     TRY(join_leaves(st));
     return device_copy(st->launch, g, st->base + st->w.g, (size_t)st->d.n_params() * 4);
 }
@@ -1051,7 +1056,7 @@ extern "C" int amdp_grad_accumulate(amdp_stage_t* st, int32_t mb) {
     const int aslot = st->find_mb(mb);
     if (aslot < 0 || !st->as[aslot].backwarded || st->staged_slot != aslot) return AMDP_E_MB_STATE;
     const long n4 = st->d.n_alloc() / 4;
-    {
+    if (!st->fused_acc) {
         // HBM-bound and needed by nothing before the next update: it runs on the
         // side stream under whatever the main stream does next (usually the
         // matrix-core-bound forward of another minibatch). The next backward's
@@ -1148,6 +1153,13 @@ extern "C" int amdp_stage_profile_end(amdp_stage_t* st, amdp_profile_entry_t* ou
 }
 
 extern "C" const char* amdp_last_hip_error(void) { return g_hip_detail; }
+
+extern "C" int amdp_stage_set_fused_accumulate(amdp_stage_t* st, int32_t on) {
+    if (!st) return AMDP_E_INVAL;
+    if (st->staged_slot >= 0) return AMDP_E_MB_STATE;    // between a backward and its accumulate
+    st->fused_acc = on != 0;
+    return AMDP_OK;
+}
 
 extern "C" int amdp_stage_join(amdp_stage_t* st) {
     if (!st) return AMDP_E_INVAL;

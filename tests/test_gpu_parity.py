@@ -212,6 +212,63 @@ def test_side_stream_on_off_bit_identical():
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("key", ["gpt_tile", "lmhead_tile", "bert_mid", "gpt"])
+def test_fused_accumulate_bit_identical(key):
+    """amdp_stage_set_fused_accumulate(1): backward adds into G directly. A
+    whole schedule must end in exactly the state of the two-step form; the
+    per-minibatch gradient is then not available."""
+    import torch
+    import paper_2605_29664_amd as amdp
+    from oracle.stage import Stage as OStage
+    w = W.TINY[key]
+    theta0 = W.make_theta(w, OStage.from_workload(w).layout)
+    M = 2 * w.threshold + w.act_slots
+    ev = amdp.amdp_schedule_generate(w.depth, w.pipelines, w.stage, w.threshold, M, w.inject_limit,
+                                     amdp.U_NEXT_BUBBLE, amdp.BWD_STASHED)
+    finals = []
+    for fused in (False, True):
+        gpu = GpuStage(w, act_slots=w.act_slots, stash_slots=2)
+        gpu.set_state(theta0)
+        gpu.stage.amdp_stage_set_fused_accumulate(fused)
+        dt = gpu.dt
+        y = torch.empty(1, dtype=torch.float32, device="cuda:0") if w.has_lm_head else \
+            torch.empty((w.tokens, w.d_model), dtype=dt, device="cuda:0")
+        dx = torch.empty((w.tokens, w.d_model), dtype=dt, device="cuda:0")
+        keep, sums = [], []
+        n_partial = 0
+        for e in ev:
+            if e.kind == amdp.EV_F:
+                x = gpu.to_dev(W.make_x(w, e.mb), dt)
+                from tests.parity import aux_for
+                a = aux_for(w, e.mb)
+                a = None if a is None else gpu.to_dev(np.asarray(a, dtype=np.int32))
+                keep += [x, a]
+                gpu.stage.amdp_stage_forward(e.mb, e.version, x, a, y)
+            elif e.kind == amdp.EV_B:
+                dy = None if w.has_lm_head else gpu.to_dev(W.make_dy(w, e.mb), dt)
+                keep.append(dy)
+                gpu.stage.amdp_stage_backward(e.mb, e.version, dy, dx)
+                if fused and n_partial == 0:
+                    n_partial = 1
+                    with pytest.raises(amdp.AmdpError):
+                        gpu.stage.amdp_stage_get_staged_grad(torch.empty(gpu.n, dtype=torch.float32, device="cuda:0"))
+                    with pytest.raises(amdp.AmdpError):      # not between a backward and its accumulate
+                        gpu.stage.amdp_stage_set_fused_accumulate(False)
+            elif e.kind == amdp.EV_A:
+                gpu.stage.amdp_grad_accumulate(e.mb)
+            else:
+                sums.append(gpu.state()["G"])           # the window's gradient sum, just before it is applied
+                gpu.stage.amdp_apply_update(w.lr, w.beta1, w.beta2, w.eps, w.weight_decay, 1.0 / w.threshold, True)
+        s = gpu.state()
+        torch.cuda.synchronize()
+        finals.append([s["theta"], s["m"], s["v"], dx.float().cpu().numpy()] + sums)
+        gpu.stage.close()
+    assert np.any(finals[0][0] != theta0) and all(np.any(G != 0.0) for G in finals[0][4:])
+    assert len(finals[0]) == len(finals[1]) >= 6
+    for k, (a, b) in enumerate(zip(*finals)):
+        assert np.array_equal(a, b), k
+
+
 def test_hip_graph_replay_matches_eager():
     """Forward + backward + accumulate captured once in a HIP graph (the library
     clears and copies with its own kernels and forks / joins its side stream
