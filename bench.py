@@ -67,7 +67,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus must be 1 "
-              "(no multi-GPU path exists, see DESIGN.md 'How the path would shard')", file=sys.stderr)
+              "(there is no multi-GPU path: stages would be joined by one transfer per event and replicas of a "
+              "stage by one gradient reduction per update)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -31,16 +31,21 @@ _LAYER_FIELDS = ("ln1_gamma", "ln1_beta", "w_qkv", "b_qkv", "w_o", "b_o",
                  "ln2_gamma", "ln2_beta", "w_1", "b_1", "w_2", "b_2")
 
 
-def param_layout(n_layers, d_model, d_ffn, has_lm_head=False, vocab=0):
-    """Flat parameter order: per layer gamma1, beta1, W_qkv [D,3D], b_qkv,
-    W_o [D,D], b_o, gamma2, beta2, W_1 [D,F], b_1, W_2 [F,D], b_2; on the last
-    stage then final gamma, beta and the tied embedding E [V,D].
-    Returns a list of (name, offset, rows, cols)."""
+def param_layout(n_layers, d_model, d_ffn, has_lm_head=False, vocab=0, has_embedding=False, seq_len=0):
+    """Flat parameter order: on the first stage the token embedding E [V,D] and
+    the learned position embedding [s,D]; per layer gamma1, beta1, W_qkv
+    [D,3D], b_qkv, W_o [D,D], b_o, gamma2, beta2, W_1 [D,F], b_1, W_2 [F,D],
+    b_2; on the last stage then final gamma, beta and the tied embedding E
+    [V,D]. Returns a list of (name, offset, rows, cols)."""
     D, Fd = d_model, d_ffn
     shapes = {"ln1_gamma": (1, D), "ln1_beta": (1, D), "w_qkv": (D, 3 * D), "b_qkv": (1, 3 * D),
               "w_o": (D, D), "b_o": (1, D), "ln2_gamma": (1, D), "ln2_beta": (1, D),
               "w_1": (D, Fd), "b_1": (1, Fd), "w_2": (Fd, D), "b_2": (1, D)}
     out, off = [], 0
+    if has_embedding:
+        for name, (r, c) in (("tok_embed", (vocab, D)), ("pos_embed", (seq_len, D))):
+            out.append((name, off, r, c))
+            off += r * c
     for l in range(n_layers):
         for f in _LAYER_FIELDS:
             r, c = shapes[f]
@@ -226,30 +231,45 @@ class Stage:
     """Shape record plus forward/backward over a flat parameter vector."""
 
     def __init__(self, block_kind, n_layers, d_model, n_heads, d_ffn, seq_len, microbatch,
-                 has_lm_head=False, vocab=0, ln_eps=1e-5):
+                 has_lm_head=False, vocab=0, ln_eps=1e-5, has_embedding=False):
         self.kind, self.L, self.D, self.H, self.Fd = block_kind, n_layers, d_model, n_heads, d_ffn
         self.s, self.b = seq_len, microbatch
         self.has_lm_head, self.V, self.eps = bool(has_lm_head), vocab, ln_eps
-        self.layout = param_layout(n_layers, d_model, d_ffn, has_lm_head, vocab)
+        self.has_embedding = bool(has_embedding)
+        if self.has_embedding and self.has_lm_head:
+            raise ValueError("a stage holds the input embedding or the output head, not both")
+        self.layout = param_layout(n_layers, d_model, d_ffn, has_lm_head, vocab, has_embedding, seq_len)
         self.n_params = n_params(self.layout)
 
     @classmethod
     def from_workload(cls, w):
         return cls(w.block_kind, w.n_layers, w.d_model, w.n_heads, w.d_ffn, w.seq_len,
-                   w.microbatch, w.has_lm_head, w.vocab, w.ln_eps)
+                   w.microbatch, w.has_lm_head, w.vocab, w.ln_eps, getattr(w, "has_embedding", False))
 
     def forward(self, theta, x, aux=None):
         """Returns (Y or scalar loss, saved). `aux` is valid_len[b] for the
-        bidirectional block, targets[N] on the LM-head stage."""
+        bidirectional block, targets[N] on the LM-head stage. On the first
+        stage (input embedding) x is ignored and aux holds the token ids [N],
+        followed by valid_len[b] for the bidirectional block: the block input
+        is the token's embedding row plus the learned embedding of its
+        position (the model family's input layer, Section 4.1)."""
         p = unpack(np.asarray(theta, dtype=np.float64), self.layout)
-        h = np.asarray(x, dtype=np.float64)
+        tokens = None
+        if self.has_embedding:
+            N = self.s * self.b
+            aux = np.asarray(aux)
+            tokens = aux[:N].astype(np.int64)
+            aux = aux[N:] if self.kind == BERT_POSTLN_BIDIR else None
+            h = p["tok_embed"][tokens] + np.tile(p["pos_embed"], (self.b, 1))
+        else:
+            h = np.asarray(x, dtype=np.float64)
         valid = aux if (self.kind == BERT_POSTLN_BIDIR and not self.has_lm_head) else None
         saved = []
         for l in range(self.L):
             h, sv = block_fwd(h, p, l, self.kind, self.H, self.s, valid, self.eps)
             saved.append(sv)
         if not self.has_lm_head:
-            return h, (saved, None)
+            return h, (saved, tokens)
         z, lnf = layernorm_fwd(h, p["lnf_gamma"], p["lnf_beta"], self.eps)
         logits = z @ p["embed"].T
         mx = logits.max(axis=1, keepdims=True)
@@ -279,6 +299,11 @@ class Stage:
             d = np.asarray(dy, dtype=np.float64)
         for l in reversed(range(self.L)):
             d = block_bwd(d, blocks[l], p, l, self.kind, self.H, self.s, g)
+        if self.has_embedding:
+            tokens = head
+            g["tok_embed"] = np.zeros((self.V, self.D))
+            np.add.at(g["tok_embed"], tokens, d)                 # rows of repeated tokens add up
+            g["pos_embed"] = d.reshape(self.b, self.s, self.D).sum(axis=0)
         flat = np.zeros(self.n_params)
         for name, off, r, c in self.layout:
             flat[off:off + r * c] = np.asarray(g[name]).reshape(-1)

@@ -43,6 +43,9 @@ def make_cfg(w, **kw):
 def aux_for(w, mb):
     if w.has_lm_head:
         return W.make_targets(w, mb)
+    if w.has_embedding:          # token ids, then the padding mask for the bidirectional block
+        t = W.make_tokens(w, mb)
+        return np.concatenate([t, W.make_valid_len(w, mb)]) if w.block_kind == W.configs.BERT_POSTLN_BIDIR else t
     if w.block_kind == W.configs.BERT_POSTLN_BIDIR:
         return W.make_valid_len(w, mb)
     return None

@@ -220,3 +220,73 @@ def test_table2_parameter_counts(golden_dir):
     bert = (b["layers"] * per_layer + 29056 * h + 512 * h + 2 * h + (h * h + h)
             + (h * h + h) + 2 * h + 29056 + (2 * h + 2) + 2 * h)
     assert bert == b["params"]
+
+
+# ------------------------------------------------ first stage: input embedding
+def _embed_setup(bert=False):
+    w = W.TINY["embed"]
+    if bert:
+        w = w.with_(block_kind=W.configs.BERT_POSTLN_BIDIR)
+    st = Stage.from_workload(w)
+    theta = W.make_theta(w, st.layout).astype(np.float64)
+    tokens = W.make_tokens(w, 0)
+    aux = np.concatenate([tokens, np.array([5, 8], dtype=np.int32)]) if bert else tokens
+    dy = W.make_dy(w, 0).astype(np.float64) * 1e3
+    return w, st, theta, tokens, aux, dy
+
+
+@pytest.mark.parametrize("bert", [False, True])
+def test_embedding_stage_matches_autograd(bert):
+    """Token + learned position embedding in front of the blocks, against
+    torch.nn.functional.embedding feeding the independent torch model."""
+    w, st, theta, tokens, aux, dy = _embed_setup(bert)
+    assert [n for n, *_ in st.layout[:2]] == ["tok_embed", "pos_embed"]
+    out, saved = st.forward(theta, None, aux)
+    dx, g = st.backward(theta, saved, dy)
+    V, D, s, b = w.vocab, w.d_model, w.seq_len, w.microbatch
+    tt = torch.tensor(theta, dtype=F64, requires_grad=True)
+    E, P = tt[: V * D].view(V, D), tt[V * D: V * D + s * D].view(s, D)
+    x = TF.embedding(torch.as_tensor(tokens, dtype=torch.long), E) + P.repeat(b, 1)
+    body = w.with_(has_embedding=False)
+    ref = torch_stage(body, tt[V * D + s * D:], x, aux[len(tokens):] if bert else None)
+    assert np.allclose(out, ref.detach().numpy(), rtol=1e-11, atol=1e-12)
+    ref.backward(torch.tensor(dy, dtype=F64))
+    assert np.allclose(g, tt.grad.numpy(), rtol=1e-9, atol=1e-12)
+
+
+def test_embedding_gradient_structure():
+    """Rows of tokens that do not occur get exactly zero; a token that occurs k
+    times gets the sum of k rows of the input gradient; the position gradient
+    is the sum over the sequences of the minibatch."""
+    w, st, theta, tokens, aux, dy = _embed_setup()
+    _, saved = st.forward(theta, None, aux)
+    _, g = st.backward(theta, saved, dy)
+    V, D, s, b = w.vocab, w.d_model, w.seq_len, w.microbatch
+    gE, gP = g[: V * D].reshape(V, D), g[V * D: V * D + s * D].reshape(s, D)
+    counts = np.bincount(tokens, minlength=V)
+    assert counts.max() >= 2 and counts.min() == 0          # the case has repeats and absentees
+    assert np.all(gE[counts == 0] == 0.0)
+    # the gradient that reaches the block input, recovered from a body-only stage
+    body = Stage.from_workload(w.with_(has_embedding=False))
+    x = theta[: V * D].reshape(V, D)[tokens] + np.tile(theta[V * D: V * D + s * D].reshape(s, D), (b, 1))
+    _, sv = body.forward(theta[V * D + s * D:], x)
+    dx, gb = body.backward(theta[V * D + s * D:], sv, dy)
+    assert np.array_equal(g[V * D + s * D:], gb)
+    for t in np.flatnonzero(counts):
+        assert np.allclose(gE[t], dx[tokens == t].sum(axis=0), rtol=1e-12, atol=1e-14)
+    assert np.allclose(gP, dx.reshape(b, s, D).sum(axis=0), rtol=1e-12, atol=1e-14)
+
+
+def test_embedding_finite_differences():
+    w, st, theta, tokens, aux, dy = _embed_setup()
+    _, saved = st.forward(theta, None, aux)
+    _, g = st.backward(theta, saved, dy)
+    scalar = lambda th: float((st.forward(th, None, aux)[0] * dy).sum())
+    rng = np.random.default_rng(11)
+    n_emb = (w.vocab + w.seq_len) * w.d_model
+    for j in rng.choice(n_emb, size=40, replace=False):
+        tp, tm = theta.copy(), theta.copy()
+        tp[j] += 1e-5
+        tm[j] -= 1e-5
+        fd = (scalar(tp) - scalar(tm)) / 2e-5
+        assert abs(fd - g[j]) <= 1e-6 * max(1.0, abs(fd)) + 1e-9, (j, fd, g[j])

@@ -28,6 +28,7 @@ class StageWorkload:
     dtype: int
     has_lm_head: bool = False
     vocab: int = 0
+    has_embedding: bool = False   # first stage: token + learned position embedding in front of the blocks
     # schedule
     depth: int = 4
     pipelines: int = 2
@@ -88,6 +89,13 @@ TINY = {
     "lmhead": StageWorkload("tiny_lmhead", 13, GPT_PRELN_CAUSAL, 2, 16, 2, 40, 8, 2, FP32,
                             has_lm_head=True, vocab=37,
                             depth=4, pipelines=2, stage=3, threshold=4),
+    # first stages: token ids in, small vocabularies so that tokens repeat inside a minibatch
+    "embed": StageWorkload("tiny_embed", 26, GPT_PRELN_CAUSAL, 2, 16, 2, 40, 8, 2, FP32, vocab=11,
+                           has_embedding=True, depth=4, pipelines=2, stage=0, threshold=4),
+    "embed_tile": StageWorkload("tile_embed", 27, GPT_PRELN_CAUSAL, 1, 256, 4, 1024, 256, 2, BF16, vocab=301,
+                                has_embedding=True, depth=4, pipelines=2, stage=0, threshold=4),
+    "embed_bert_mid": StageWorkload("mid_embed_bert", 28, BERT_POSTLN_BIDIR, 1, 192, 3, 448, 200, 3, BF16, vocab=1031,
+                                    has_embedding=True, depth=4, pipelines=2, stage=0, threshold=4),
     # medium shapes: several GPU tiles plus a ragged tail, still seconds on CPU
     "gpt_mid": StageWorkload("mid_gpt", 14, GPT_PRELN_CAUSAL, 2, 192, 3, 448, 200, 2, BF16,
                              depth=6, pipelines=3, stage=2, threshold=6),

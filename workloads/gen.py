@@ -69,3 +69,9 @@ def make_valid_len(workload, mb):
 def make_targets(workload, mb):
     rng = np.random.default_rng(seed_for(workload, 700000 + mb))
     return rng.integers(0, workload.vocab, size=workload.tokens).astype(np.int32)
+
+
+def make_tokens(workload, mb):
+    """Token ids of a first-stage minibatch, uniform over the vocabulary."""
+    rng = np.random.default_rng(seed_for(workload, 900000 + mb))
+    return rng.integers(0, workload.vocab, size=workload.tokens).astype(np.int32)
