@@ -102,7 +102,8 @@ def main():
         aux = [torch.from_numpy(W.make_targets(w, k)).to(dev) for k in range(ring)]
         outs = [torch.empty(1, dtype=torch.float32, device=dev) for _ in range(ring)]
     else:
-        aux = [torch.from_numpy(W.make_valid_len(w, k)).to(dev) if w.block_kind == 1 else None
+        from tests.parity import aux_for      # token ids (+ padding mask) on a first stage, padding mask for BERT
+        aux = [None if aux_for(w, k) is None else torch.from_numpy(np.asarray(aux_for(w, k), dtype=np.int32)).to(dev)
                for k in range(ring)]
         outs = [torch.empty((w.tokens, w.d_model), dtype=dt, device=dev) for _ in range(ring)]
     dX = torch.empty((w.tokens, w.d_model), dtype=dt, device=dev)
@@ -154,7 +155,9 @@ def main():
         "vs_baseline": None, "dtype": "bf16" if w.dtype == 1 else "f32", "data": "synthetic",
         "config": {"workload": w.name, "block": "gpt_preln_causal" if w.block_kind == 0 else "bert_postln_bidir",
                    "layers": w.n_layers, "d_model": w.d_model, "heads": w.n_heads, "d_ffn": w.d_ffn,
-                   "seq_len": w.seq_len, "microbatch": w.microbatch, "vocab": w.vocab if w.has_lm_head else 0,
+                   "seq_len": w.seq_len, "microbatch": w.microbatch,
+                   "vocab": w.vocab if (w.has_lm_head or w.has_embedding) else 0,
+                   "input_embedding": bool(w.has_embedding),
                    "depth": w.depth, "pipelines": P, "stage": w.stage, "minibatches_per_update": T,
                    "tokens_per_step": T * w.tokens, "parallelism": "1 stage on 1 GPU",
                    "accumulation": "fused into backward" if args.fused_accumulate else "own kernel per minibatch"},
@@ -258,6 +261,7 @@ def cpu_baseline(w):
     import workloads as W
     from oracle import optim
     from oracle.stage import Stage as OStage
+    from tests.parity import aux_for
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
@@ -270,7 +274,7 @@ def cpu_baseline(w):
     n_mb, t0 = 0, time.perf_counter()
     while n_mb < 4 and (n_mb == 0 or time.perf_counter() - t0 < 12.0):
         x = W.make_x(w, n_mb)
-        aux = W.make_targets(w, n_mb) if w.has_lm_head else (W.make_valid_len(w, n_mb) if w.block_kind == 1 else None)
+        aux = aux_for(w, n_mb)
         dy = None if w.has_lm_head else W.make_dy(w, n_mb)
         _, saved = ost.forward(theta, x, aux)
         _, g = ost.backward(theta, saved, dy)

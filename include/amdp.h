@@ -201,6 +201,9 @@ typedef struct amdp_stage_config_t {
     float   ln_eps;
     int32_t act_slots;    /* minibatches that may be in flight (>= w*P) */
     int32_t stash_slots;  /* weight versions kept besides the current one (>= 1) */
+    int32_t has_embedding; /* first stage: the block input is E[token] + P[position] (token and learned
+                              position embedding, V = vocab rows and s rows of D); excludes has_lm_head;
+                              d_model <= 8192 */
 } amdp_stage_config_t;
 
 typedef struct amdp_stage amdp_stage_t;
@@ -209,7 +212,9 @@ typedef struct amdp_stage amdp_stage_t;
  * W_qkv [D,3D] (columns Q|K|V, each split into H heads of D/H), b_qkv [3D];
  * W_o [D,D], b_o [D]; ln2 gamma, beta [D]; W_1 [D,F], b_1 [F]; W_2 [F,D], b_2 [D]
  * -- 12D^2+13D per layer when F = 4D, the count behind Table 2. With an LM head:
- * then final gamma, beta [D] and the tied embedding E [V,D]. Matrices are
+ * then final gamma, beta [D] and the tied embedding E [V,D]. With an input
+ * embedding: in front of the layers, the token embedding [V,D] and the position
+ * embedding [s,D]. Matrices are
  * row-major [in, out]; y = x W + b. */
 typedef struct amdp_param_desc_t {
     char     name[24];   /* e.g. "l0.w_qkv", "lnf_gamma", "embed" */
@@ -254,8 +259,11 @@ int amdp_stage_resident_versions(amdp_stage_t* stage, uint32_t* versions, int32_
 
 /* Forward of minibatch `mb` with weight version `version` (Section 3.1: the
  * version is whatever the schedule assigns; it must be resident).
- *   X    device [N, D] token-major (row = sequence*s + position), stage dtype
- *   aux  device int32: valid_len[b] for the BERT block (keys at positions >=
+ *   X    device [N, D] token-major (row = sequence*s + position), stage dtype;
+ *        ignored (may be NULL) on a stage with an input embedding
+ *   aux  device int32: on a stage with an input embedding the token ids [N]
+ *        (ids outside [0, V) are clamped), followed by valid_len[b] for the BERT
+ *        block; otherwise valid_len[b] for the BERT block (keys at positions >=
  *        valid_len are masked; each entry in [1, s] -- a sequence with no
  *        visible key has no softmax and the library does not check device
  *        data), targets[N] in [0, V) on an LM-head stage, else NULL
@@ -309,6 +317,17 @@ int amdp_apply_update(amdp_stage_t* stage, const amdp_adam_t* hp, uint32_t* new_
  * on = 0 keeps everything on the caller's stream (used to time kernels in
  * isolation); default is on. Results are bit-identical either way. */
 int amdp_stage_set_overlap(amdp_stage_t* stage, int32_t on);
+
+/* The input embedding of the first stage and the output projection of the last
+ * are one tied parameter held twice; before the update their gradient sums must
+ * be added. first: a stage with has_embedding, last: a stage with has_lm_head,
+ * same vocab and d_model. Afterwards both hold the sum in their G (token
+ * embedding rows resp. tied embedding rows), so both updates move their copy
+ * alike. On one GPU this is a local two-buffer sum; across GPUs it would be the
+ * one transfer the tie costs per update. Both stages' pending work is joined;
+ * the sum runs on `first`'s stream, which the caller must have ordered after
+ * `last`'s stream (the same stream is the simple case). */
+int amdp_tie_embedding_grads(amdp_stage_t* first, amdp_stage_t* last);
 
 /* on = 1: backward adds the minibatch's parameter gradients straight into the
  * sum G (the dW products and the column sums end in G += instead of g =), and

@@ -6,7 +6,7 @@ from .binding import (  # noqa: F401
     AmdpError, lib, lib_path, build,
     amdp_event_t, amdp_sched_params_t, amdp_sched_stats_t, amdp_stage_config_t,
     amdp_param_desc_t, amdp_adam_t, amdp_profile_entry_t, make_config,
-    amdp_sim_params_t, amdp_sim_op_t, amdp_sim_result_t, amdp_system_simulate,
+    amdp_sim_params_t, amdp_sim_op_t, amdp_sim_result_t, amdp_system_simulate, amdp_tie_embedding_grads,
     amdp_strerror, amdp_schedule_generate, amdp_schedule_stats, amdp_stage_map,
     amdp_stage_n_params, amdp_stage_workspace_bytes, amdp_stage_param_layout,
     Stage,

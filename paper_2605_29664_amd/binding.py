@@ -66,7 +66,7 @@ class amdp_stage_config_t(C.Structure):
                 ("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ffn", C.c_int32),
                 ("seq_len", C.c_int32), ("microbatch", C.c_int32), ("dtype", C.c_int32),
                 ("has_lm_head", C.c_int32), ("vocab", C.c_int32), ("ln_eps", C.c_float),
-                ("act_slots", C.c_int32), ("stash_slots", C.c_int32)]
+                ("act_slots", C.c_int32), ("stash_slots", C.c_int32), ("has_embedding", C.c_int32)]
 
 
 class amdp_param_desc_t(C.Structure):
@@ -150,6 +150,7 @@ def lib():
         "amdp_stage_set_overlap": (C.c_int, [vp, i32]),
         "amdp_stage_join": (C.c_int, [vp]),
         "amdp_stage_set_fused_accumulate": (C.c_int, [vp, i32]),
+        "amdp_tie_embedding_grads": (C.c_int, [vp, vp]),
         "amdp_stage_profile_begin": (C.c_int, [vp]),
         "amdp_stage_profile_end": (C.c_int, [vp, P(amdp_profile_entry_t), i32, P(i32)]),
     }
@@ -167,7 +168,7 @@ EXPORTED = ["amdp_strerror", "amdp_last_hip_error", "amdp_schedule_generate", "a
             "amdp_stage_create", "amdp_stage_destroy", "amdp_stage_set_state", "amdp_stage_get_state",
             "amdp_stage_get_staged_grad", "amdp_stage_resident_versions", "amdp_stage_forward",
             "amdp_stage_backward", "amdp_grad_accumulate", "amdp_apply_update",
-            "amdp_stage_set_overlap", "amdp_stage_join", "amdp_stage_set_fused_accumulate",
+            "amdp_stage_set_overlap", "amdp_stage_join", "amdp_stage_set_fused_accumulate", "amdp_tie_embedding_grads",
             "amdp_stage_profile_begin", "amdp_stage_profile_end"]
 
 
@@ -224,11 +225,16 @@ def amdp_system_simulate(depth, pipelines, minibatches, t_forward=1, t_backward=
                      busy_total=res.busy_total, busy_min=res.busy_min, busy_max=res.busy_max)
 
 
+def amdp_tie_embedding_grads(first, last):
+    """first, last: Stage objects (input-embedding stage, LM-head stage)."""
+    _check(lib().amdp_tie_embedding_grads(first.handle, last.handle), "amdp_tie_embedding_grads")
+
+
 def make_config(block_kind, n_layers, d_model, n_heads, d_ffn, seq_len, microbatch, dtype,
-                has_lm_head=False, vocab=0, ln_eps=1e-5, act_slots=4, stash_slots=1):
+                has_lm_head=False, vocab=0, ln_eps=1e-5, act_slots=4, stash_slots=1, has_embedding=False):
     return amdp_stage_config_t(C.sizeof(amdp_stage_config_t), block_kind, n_layers, d_model, n_heads,
                                d_ffn, seq_len, microbatch, dtype, int(bool(has_lm_head)), vocab, ln_eps,
-                               act_slots, stash_slots)
+                               act_slots, stash_slots, int(bool(has_embedding)))
 
 
 def amdp_stage_n_params(cfg):
@@ -339,6 +345,10 @@ class Stage:
         if self.cfg.has_lm_head:
             a = _ptr(aux, torch.int32, self.tokens, self.device)
             o = _ptr(out, torch.float32, 1, self.device)
+        elif self.cfg.has_embedding:
+            n_aux = self.tokens + (self.cfg.microbatch if self.cfg.block_kind == BLOCK_BERT else 0)
+            a = _ptr(aux, torch.int32, n_aux, self.device)
+            o = self._act(out)
         else:
             a = _ptr(aux, torch.int32, self.cfg.microbatch, self.device)
             o = self._act(out)

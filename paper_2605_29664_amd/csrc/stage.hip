@@ -5,6 +5,7 @@
 // accumulate and update. Everything is enqueued on one HIP stream.
 #include "amdp.h"
 #include "attention.h"
+#include "embedding.h"
 #include "common.h"
 #include "gemm_mfma.h"
 #include "gemm_simple.h"
@@ -38,6 +39,7 @@ struct Dims {
     int L, D, H, dh, F, s, b, N, V;
     long Vld;
     bool lm, bf, causal;
+    bool emb = false;      // first stage: token + position embedding in front of the blocks
     size_t esz;
     long field_size(int f) const {
         switch (f) {
@@ -55,14 +57,17 @@ struct Dims {
         for (int f = 0; f < N_FIELDS; ++f) t += field_size(f);
         return t;
     }
+    long emb_params() const { return emb ? ((long)V + s) * D : 0; }
+    long off_tok() const { return 0; }
+    long off_pos() const { return (long)V * D; }
     long off(int layer, int f) const {
-        long t = layer * layer_params();
+        long t = emb_params() + layer * layer_params();
         for (int k = 0; k < f; ++k) t += field_size(k);
         return t;
     }
-    long off_lnf() const { return L * layer_params(); }
+    long off_lnf() const { return emb_params() + L * layer_params(); }
     long off_embed() const { return off_lnf() + 2L * D; }
-    long n_params() const { return lm ? off_embed() + (long)V * D : L * layer_params(); }
+    long n_params() const { return lm ? off_embed() + (long)V * D : emb_params() + L * layer_params(); }
     long n_alloc() const {
         long n = n_params() + (lm ? (long)LM_PAD_ROWS * D : 0);
         return (long)round_up((size_t)n, 1024);
@@ -78,7 +83,9 @@ bool make_dims(const amdp_stage_config_t* c, Dims* d) {
         c->microbatch < 1)
         return false;
     if (c->d_model % c->n_heads) return false;
-    if (c->has_lm_head && c->vocab < 1) return false;
+    if ((c->has_lm_head || c->has_embedding) && c->vocab < 1) return false;
+    if (c->has_lm_head && c->has_embedding) return false;   // input layer or output head, not both
+    if (c->has_embedding && c->d_model > 8192) return false; // width of the token-gradient kernel
     if (c->act_slots < 1 || c->act_slots > MAX_ASLOTS) return false;
     if (c->stash_slots < 1 || c->stash_slots + 1 > MAX_VSLOTS) return false;
     if (!(c->ln_eps > 0.f)) return false;
@@ -87,7 +94,7 @@ bool make_dims(const amdp_stage_config_t* c, Dims* d) {
     if ((long)c->seq_len * c->microbatch > (1L << 24)) return false;
     d->L = c->n_layers; d->D = c->d_model; d->H = c->n_heads; d->dh = c->d_model / c->n_heads;
     d->F = c->d_ffn; d->s = c->seq_len; d->b = c->microbatch; d->N = c->seq_len * c->microbatch;
-    d->lm = c->has_lm_head != 0; d->V = d->lm ? c->vocab : 0;
+    d->lm = c->has_lm_head != 0; d->emb = c->has_embedding != 0; d->V = (d->lm || d->emb) ? c->vocab : 0;
     d->Vld = d->lm ? (long)round_up((size_t)d->V, LM_PAD_ROWS) : 0;
     d->bf = c->dtype == AMDP_BF16; d->esz = d->bf ? 2 : 4;
     d->causal = c->block_kind == AMDP_BLOCK_GPT_PRELN_CAUSAL;
@@ -102,6 +109,7 @@ struct SlotLayout {
     std::vector<LayerAct> layers;
     size_t yL = 0, z = 0, stf = 0, dlogits = 0;
     size_t valid = 0;   // copy of the padding mask (valid_len[b]) for backward
+    size_t tokens = 0;  // copy of the token ids [N] of a first stage, for backward
     size_t bytes = 0;
 };
 struct Carve {
@@ -159,6 +167,7 @@ void carve(const Dims& d, const amdp_stage_config_t& c, Carve* w) {
             w->slot.dlogits = st((size_t)d.N * d.Vld * d.esz);
         }
         w->slot.valid = st((size_t)d.b * 4);
+        w->slot.tokens = st(d.emb ? (size_t)d.N * 4 : 0);
         w->slot.bytes = so;
     }
     w->slot_bytes = w->slot.bytes;
@@ -671,10 +680,18 @@ int forward_impl(amdp_stage* st, int aslot, int vslot, const void* X, const int3
     const T* W = (const T*)st->version_ptr(vslot);
     char* S = st->act_ptr(aslot);
     const size_t ND = (size_t)d.N * d.D * sizeof(T);
-    // aux is the padding mask for bidirectional blocks, the targets on an LM-head stage
-    const int32_t* valid = (!d.causal && !d.lm) ? aux : nullptr;
+    // aux is the padding mask for bidirectional blocks, the targets on an LM-head
+    // stage, and on a first stage the token ids followed by the padding mask
+    const int32_t* valid = (!d.causal && !d.lm) ? (d.emb ? aux + d.N : aux) : nullptr;
     if (valid) TRY(device_copy(st->launch, S + st->w.slot.valid, valid, (size_t)d.b * 4));
-    {
+    if (d.emb) {
+        TRY(device_copy(st->launch, S + st->w.slot.tokens, aux, (size_t)d.N * 4));
+        ProfScope ps(st, "embedding_fwd", 0.0, 3.0 * (double)ND);
+        hipLaunchKernelGGL(embed_fwd_kernel<T>, dim3((d.N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0,
+                           st->launch, W + d.off_tok(), W + d.off_pos(), aux, (T*)(S + st->w.slot.layers[0].xin),
+                           d.N, d.s, d.D, d.V);
+        TRY(after_launch());
+    } else {
         ProfScope ps(st, "copy_input", 0.0, 2.0 * (double)ND);
         TRY(device_copy(st->launch, S + st->w.slot.layers[0].xin, X, ND));
     }
@@ -834,6 +851,23 @@ int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, co
         }
         dcur = dnext;
     }
+    if (d.emb) {
+        // gradient of the input layer from dcur = d loss / d (block input)
+        const int32_t* tokens = (const int32_t*)(S + st->w.slot.tokens);
+        const int acc = st->fused_acc ? 1 : 0;
+        LEAF({
+            ProfScope ps(st, "embedding_bwd", 0.0, 2.0 * (double)d.N * d.D * sizeof(T));
+            const long pv = (long)d.s * (d.D / Vec<T>::N);
+            hipLaunchKernelGGL(pos_embed_bwd_kernel<T>, dim3((unsigned)((pv + 255) / 256)), dim3(256), 0, st->launch,
+                               (const T*)dcur, g + d.off_pos(), d.b, d.s, d.D, acc);
+            TRY(after_launch());
+            // rows of absent tokens are zero in a minibatch's own gradient
+            if (!acc) TRY(device_zero(st->launch, g + d.off_tok(), (size_t)d.V * d.D * 4));
+            hipLaunchKernelGGL((tok_embed_bwd_kernel<T, 32 / Vec<T>::N>), dim3(d.N), dim3(256), 0, st->launch,
+                               (const T*)dcur, tokens, g + d.off_tok(), d.N, d.D, d.V, acc);
+            TRY(after_launch());
+        });
+    }
     return join_leaves(st);
 }
 
@@ -866,7 +900,7 @@ extern "C" int amdp_stage_param_layout(const amdp_stage_config_t* cfg, amdp_para
                                        int32_t* n) {
     Dims d;
     if (!make_dims(cfg, &d) || !n) return AMDP_E_INVAL;
-    const int total = d.L * N_FIELDS + (d.lm ? 3 : 0);
+    const int total = d.L * N_FIELDS + (d.lm ? 3 : 0) + (d.emb ? 2 : 0);
     *n = total;
     if (cap < total || !descs) return AMDP_E_CAPACITY;
     int k = 0;
@@ -876,6 +910,10 @@ extern "C" int amdp_stage_param_layout(const amdp_stage_config_t* cfg, amdp_para
         descs[k].offset = (uint64_t)off; descs[k].rows = (uint32_t)rows; descs[k].cols = (uint32_t)cols;
         ++k;
     };
+    if (d.emb) {
+        put("tok_embed", d.off_tok(), d.V, d.D);
+        put("pos_embed", d.off_pos(), d.s, d.D);
+    }
     for (int l = 0; l < d.L; ++l)
         for (int f = 0; f < N_FIELDS; ++f) {
             char name[24];
@@ -1010,9 +1048,10 @@ extern "C" int amdp_stage_resident_versions(amdp_stage_t* st, uint32_t* versions
 
 extern "C" int amdp_stage_forward(amdp_stage_t* st, int32_t mb, uint32_t version, const void* X,
                                   const int32_t* aux, void* out) {
-    if (!st || !X || !out || st->cur_slot < 0) return AMDP_E_INVAL;
+    if (!st || !out || st->cur_slot < 0) return AMDP_E_INVAL;
     const Dims& d = st->d;
-    if ((d.lm || !d.causal) && !aux) return AMDP_E_INVAL;
+    if (!X && !d.emb) return AMDP_E_INVAL;
+    if ((d.lm || d.emb || !d.causal) && !aux) return AMDP_E_INVAL;
     if (st->find_mb(mb) >= 0) return AMDP_E_MB_STATE;
     const int vslot = st->find_version(version);
     if (vslot < 0) return AMDP_E_VERSION;
@@ -1153,6 +1192,19 @@ extern "C" int amdp_stage_profile_end(amdp_stage_t* st, amdp_profile_entry_t* ou
 }
 
 extern "C" const char* amdp_last_hip_error(void) { return g_hip_detail; }
+
+extern "C" int amdp_tie_embedding_grads(amdp_stage_t* first, amdp_stage_t* last) {
+    if (!first || !last || !first->d.emb || !last->d.lm || first->d.V != last->d.V || first->d.D != last->d.D)
+        return AMDP_E_INVAL;
+    if (first->staged_slot >= 0 || last->staged_slot >= 0) return AMDP_E_MB_STATE;
+    TRY(join_leaves(first));
+    TRY(join_leaves(last));
+    const long n4 = (long)first->d.V * first->d.D / 4;
+    hipLaunchKernelGGL(tie_sum_kernel, dim3(direct_grid(n4, 64)), dim3(64), 0, first->stream,
+                       first->at<float>(first->w.G) + first->d.off_tok(),
+                       last->at<float>(last->w.G) + last->d.off_embed(), n4);
+    return after_launch();
+}
 
 extern "C" int amdp_stage_set_fused_accumulate(amdp_stage_t* st, int32_t on) {
     if (!st) return AMDP_E_INVAL;

@@ -35,7 +35,7 @@ def make_cfg(w, **kw):
     args = dict(block_kind=w.block_kind, n_layers=w.n_layers, d_model=w.d_model, n_heads=w.n_heads,
                 d_ffn=w.d_ffn, seq_len=w.seq_len, microbatch=w.microbatch, dtype=w.dtype,
                 has_lm_head=w.has_lm_head, vocab=w.vocab, ln_eps=w.ln_eps, act_slots=w.act_slots,
-                stash_slots=w.stash_slots)
+                stash_slots=w.stash_slots, has_embedding=w.has_embedding)
     args.update(kw)
     return binding.make_config(**args)
 

@@ -43,6 +43,18 @@ def test_paper_shaped_one_layer(key):
     assert rep["ok"], worst_entries(rep)
 
 
+@pytest.mark.timeout(900)
+def test_full_width_first_stage():
+    """Configuration 2's width with the input embedding in front (GPT-2's
+    50257-row vocabulary, 4096 token ids per minibatch): one layer, one
+    minibatch through forward, backward, accumulate, update."""
+    w = W.FIRST["first_gpt_d1024"].with_(n_layers=1)
+    print("\n[first stage, one layer at full width] start", flush=True)
+    rep = run_parity(w, threshold=1, n_minibatches=1, verbose=True, cfg_kw=dict(act_slots=1, stash_slots=1))
+    print(f"[first stage] worst={rep['worst']:.3e} {rep['seconds']:.0f}s", worst_entries(rep, 4), flush=True)
+    assert rep["ok"], worst_entries(rep)
+
+
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("k,prefix", [(2, 1024), (3, 512), (5, 256)])
 def test_full_depth_forward_one_sequence(k, prefix):

@@ -269,6 +269,72 @@ def test_fused_accumulate_bit_identical(key):
         assert np.array_equal(a, b), k
 
 
+@pytest.mark.parametrize("key", ["embed", "embed_tile", "embed_bert_mid"])
+def test_first_stage_with_input_embedding(key):
+    """Token ids in, token + position embedding in front of the blocks; the
+    vocabularies are small so that tokens repeat inside a minibatch and the
+    deterministic row sums of the token gradient are exercised."""
+    rep = run_parity(W.TINY[key], n_windows=1, verbose=False)
+    _report(key, rep)
+    assert rep["ok"], worst_entries(rep)
+
+
+def test_input_embedding_gradient_is_deterministic_and_fuses():
+    import torch
+    w = W.TINY["embed_tile"]
+    from oracle.stage import Stage as OStage
+    theta0 = W.make_theta(w, OStage.from_workload(w).layout)
+    res = []
+    for fused in (False, False, True):
+        gpu = GpuStage(w, act_slots=2, stash_slots=1)
+        gpu.set_state(theta0)
+        gpu.stage.amdp_stage_set_fused_accumulate(fused)
+        tok = gpu.to_dev(W.make_tokens(w, 0))
+        dy = gpu.to_dev(W.make_dy(w, 0), gpu.dt)
+        y = torch.empty((w.tokens, w.d_model), dtype=gpu.dt, device="cuda:0")
+        for mb in (0, 1):                        # two minibatches into the sum
+            gpu.stage.amdp_stage_forward(mb, 0, None, tok, y)
+            gpu.stage.amdp_stage_backward(mb, 0, dy, None)
+            gpu.stage.amdp_grad_accumulate(mb)
+        res.append(gpu.state()["G"])
+        gpu.stage.close()
+    assert np.any(res[0] != 0.0)
+    assert np.array_equal(res[0], res[1]) and np.array_equal(res[0], res[2])
+
+
+def test_tied_embedding_gradients_are_summed_into_both_stages():
+    import torch
+    import paper_2605_29664_amd as amdp
+    wf = W.TINY["embed_tile"].with_(vocab=1931)
+    wl = W.TINY["lmhead_tile"]
+    assert wf.vocab == wl.vocab and wf.d_model == wl.d_model
+    first, last = GpuStage(wf, act_slots=2, stash_slots=1), GpuStage(wl, act_slots=2, stash_slots=1)
+    from oracle.stage import Stage as OStage
+    first.set_state(W.make_theta(wf, OStage.from_workload(wf).layout))
+    last.set_state(W.make_theta(wl, OStage.from_workload(wl).layout))
+    y = torch.empty((wf.tokens, wf.d_model), dtype=first.dt, device="cuda:0")
+    first.stage.amdp_stage_forward(0, 0, None, first.to_dev(W.make_tokens(wf, 0)), y)
+    first.stage.amdp_stage_backward(0, 0, first.to_dev(W.make_dy(wf, 0), first.dt), None)
+    first.stage.amdp_grad_accumulate(0)
+    loss = torch.empty(1, dtype=torch.float32, device="cuda:0")
+    last.stage.amdp_stage_forward(0, 0, last.to_dev(W.make_x(wl, 0), last.dt), last.to_dev(W.make_targets(wl, 0)), loss)
+    last.stage.amdp_stage_backward(0, 0, None, None)
+    last.stage.amdp_grad_accumulate(0)
+    Gf, Gl = first.state()["G"], last.state()["G"]
+    VD = wf.vocab * wf.d_model
+    off_l = [off for name, off, r, c in amdp.amdp_stage_param_layout(last.cfg) if name == "embed"][0]
+    want = Gf[:VD] + Gl[off_l:off_l + VD]                      # fp32 addition, as the kernel does it
+    assert np.any(Gf[:VD] != 0.0) and np.any(Gl[off_l:off_l + VD] != 0.0)
+    amdp.amdp_tie_embedding_grads(first.stage, last.stage)
+    Gf2, Gl2 = first.state()["G"], last.state()["G"]
+    assert np.array_equal(Gf2[:VD], want) and np.array_equal(Gl2[off_l:off_l + VD], want)
+    assert np.array_equal(Gf2[VD:], Gf[VD:]) and np.array_equal(Gl2[:off_l], Gl[:off_l])
+    with pytest.raises(amdp.AmdpError):
+        amdp.amdp_tie_embedding_grads(last.stage, first.stage)
+    first.stage.close()
+    last.stage.close()
+
+
 def test_hip_graph_replay_matches_eager():
     """Forward + backward + accumulate captured once in a HIP graph (the library
     clears and copies with its own kernels and forks / joins its side stream

@@ -5,10 +5,10 @@ benchmark. It holds configuration records and random-input recipes only: none
 of the method's arithmetic (no transformer math, no optimizer, no schedule)
 lives here, and it imports neither the oracle nor the HIP binding.
 """
-from .configs import StageWorkload, CONFIGS, TINY, PAPER, get
+from .configs import StageWorkload, CONFIGS, TINY, PAPER, FIRST, get
 from .gen import (quantize_bf16_grid, make_theta, make_x, make_dy,
                   make_valid_len, make_targets, make_tokens, seed_for)
 
-__all__ = ["StageWorkload", "CONFIGS", "TINY", "PAPER", "get", "quantize_bf16_grid",
+__all__ = ["StageWorkload", "CONFIGS", "TINY", "PAPER", "FIRST", "get", "quantize_bf16_grid",
            "make_theta", "make_x", "make_dy", "make_valid_len", "make_targets", "make_tokens",
            "seed_for"]

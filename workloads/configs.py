@@ -142,6 +142,13 @@ PAPER = {
 }
 
 
+# First stage of configuration 2's model: token ids in, GPT-2's vocabulary.
+FIRST = {
+    "first_gpt_d1024": StageWorkload("first_gpt_d1024_bf16", 33, GPT_PRELN_CAUSAL, 4, 1024, 16, 4096, 1024, 4, BF16,
+                                     vocab=50257, has_embedding=True, depth=6, pipelines=3, stage=0, threshold=8),
+}
+
+
 def get(key):
     if isinstance(key, int):
         return CONFIGS[key]
@@ -149,6 +156,8 @@ def get(key):
         return TINY[key]
     if key in PAPER:
         return PAPER[key]
+    if key in FIRST:
+        return FIRST[key]
     if key.isdigit():
         return CONFIGS[int(key)]
     for c in CONFIGS.values():
