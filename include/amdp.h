@@ -68,7 +68,10 @@ const char* amdp_last_hip_error(void);
  *   - one update closes each window of T minibatches (Section 3.3). With
  *     AMDP_U_NEXT_BUBBLE it is applied immediately before the first backward of
  *     the next window ("during the next bubble"); with AMDP_U_EAGER right after
- *     the window's last accumulation (the setting of Lemma 1).
+ *     the window's last accumulation (the setting of Lemma 1). AMDP_U_FLUSH is
+ *     the synchronous comparison schedule of Table 1: each window is a 1F1B
+ *     schedule of its own, drained and updated before the next window's first
+ *     forward (no mismatch, one live version).
  * Version tags: a forward reads version = number of updates applied before
  * it. A backward reads its forward's version (AMDP_BWD_STASHED) or the
  * version current when it runs (AMDP_BWD_CURRENT; current - forward's tag is
@@ -77,7 +80,7 @@ const char* amdp_last_hip_error(void);
  * ------------------------------------------------------------------------ */
 
 enum { AMDP_EV_F = 0, AMDP_EV_B = 1, AMDP_EV_A = 2, AMDP_EV_U = 3 };
-enum { AMDP_U_NEXT_BUBBLE = 0, AMDP_U_EAGER = 1 };
+enum { AMDP_U_NEXT_BUBBLE = 0, AMDP_U_EAGER = 1, AMDP_U_FLUSH = 2 };
 enum { AMDP_BWD_STASHED = 0, AMDP_BWD_CURRENT = 1 };
 
 #define AMDP_FLAG_LAST_USE       1u  /* F/B: no later event reads this version */
@@ -108,6 +111,22 @@ typedef struct amdp_sched_params_t {
  * AMDP_E_CAPACITY is returned (call with out = NULL, cap = 0 to size). */
 int amdp_schedule_generate(const amdp_sched_params_t* params, amdp_event_t* out, size_t cap,
                            size_t* n_out);
+
+/* Generator settings of the schedules Table 1 compares, for one stage of one
+ * pipeline (AMDP: of d/2 merged pipelines), so that the same stage library and
+ * amdp_schedule_stats can show their mismatch and weight-version counts:
+ *   AMDP           n = 2, P = d/2, update in the next bubble, current weights in
+ *                  backward (mismatch <= 1, one version, Lemma 1)
+ *   PIPEDREAM      n = d, an update after every minibatch, stashed weights
+ *                  (d - i versions live at stage i, no mismatch in backward)
+ *   PIPEDREAM_2BW  n = d, gradients coalesced over >= d minibatches, stashed
+ *                  weights (two versions live)
+ *   SYNC_1F1B      minibatches of `microbatches` microbatches, flushed
+ * `microbatches`: window length T (0 = the preset's default: 2d for AMDP, d for
+ * 2BW; required for SYNC_1F1B). Fills *out; host only. */
+enum { AMDP_PRESET_AMDP = 0, AMDP_PRESET_PIPEDREAM = 1, AMDP_PRESET_PIPEDREAM_2BW = 2, AMDP_PRESET_SYNC_1F1B = 3 };
+int amdp_schedule_preset(int32_t preset, int32_t depth, int32_t stage, int32_t n_minibatches,
+                         int32_t microbatches, amdp_sched_params_t* out);
 
 typedef struct amdp_sched_stats_t {
     uint32_t struct_size;

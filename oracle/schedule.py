@@ -23,6 +23,9 @@ design notes of this repository):
     stage: a forward round is one forward per pipeline, a backward round one
     backward per pipeline, each backward followed at once by the accumulation
     of its gradient;
+  * a third placement, "flush", gives the synchronous comparison schedule of
+    Table 1 (1F1B with a pipeline flush): a window's minibatches are drained
+    and its update applied before the next window's first forward;
   * "next bubble" placement: the update closing window u is applied
     immediately before the first backward of window u+1 (this is the only
     placement that reproduces both statements made about Figure 5); the
@@ -36,7 +39,7 @@ from collections import namedtuple
 F, B, A, U = 0, 1, 2, 3
 KIND_NAMES = "FBAU"
 
-NEXT_BUBBLE, EAGER = 0, 1
+NEXT_BUBBLE, EAGER, FLUSH = 0, 1, 2
 STASHED, CURRENT = 0, 1
 
 FLAG_LAST_USE = 1       # last forward/backward that reads this version
@@ -58,25 +61,34 @@ def generate(depth, pipelines, stage, threshold, n_minibatches, inject_limit=2,
     if not (d >= 1 and P >= 1 and 0 <= i < d and T >= 1 and M >= 0 and n >= 1):
         raise ValueError("bad schedule parameters")
     w = min(n, d - i)                      # warm-up forwards per pipeline, Section 3.1
-    n_rounds = -(-M // P) if M else 0      # ceil
+    def one_f_one_b(first, last):
+        """1F1B per replica over minibatches [first, last): w forward rounds,
+        then backward round g / forward round g+w."""
+        n_rounds = -(-(last - first) // P) if last > first else 0      # ceil
+        fwd_round = lambda g: [(F, m) for m in range(first + g * P, min(first + (g + 1) * P, last))]
 
-    def fwd_round(g):
-        return [(F, m) for m in range(g * P, min((g + 1) * P, M))]
-
-    def bwd_round(g):
+        def bwd_round(g):
+            out = []
+            for m in range(first + g * P, min(first + (g + 1) * P, last)):
+                out += [(B, m), (A, m)]
+            return out
         out = []
-        for m in range(g * P, min((g + 1) * P, M)):
-            out += [(B, m), (A, m)]
+        for g in range(min(w, n_rounds)):
+            out += fwd_round(g)
+        for g in range(n_rounds):
+            out += bwd_round(g)
+            if g + w < n_rounds:
+                out += fwd_round(g + w)
         return out
 
-    # 1F1B per replica: w forward rounds, then backward round g / forward round g+w
-    order = []
-    for g in range(min(w, n_rounds)):
-        order += fwd_round(g)
-    for g in range(n_rounds):
-        order += bwd_round(g)
-        if g + w < n_rounds:
-            order += fwd_round(g + w)
+    if placement == FLUSH:
+        # synchronous schedule: a window is drained and its update applied before
+        # any forward of the next window (the classic 1F1B with a flush)
+        order = []
+        for first in range(0, M, T):
+            order += one_f_one_b(first, min(first + T, M))
+    else:
+        order = one_f_one_b(0, M)
 
     # place the updates
     n_updates = -(-M // T) if M else 0
@@ -85,7 +97,7 @@ def generate(depth, pipelines, stage, threshold, n_minibatches, inject_limit=2,
         if placement == NEXT_BUBBLE and kind == B and m % T == 0 and m > 0:
             seq.append((U, m // T - 1))
         seq.append((kind, m))
-        if placement == EAGER and kind == A and (m + 1) % T == 0:
+        if placement in (EAGER, FLUSH) and kind == A and ((m + 1) % T == 0 or (placement == FLUSH and m == M - 1)):
             seq.append((U, m // T))
     placed = sum(1 for k, _ in seq if k == U)
     for u in range(placed, n_updates):     # the last (possibly short) window

@@ -132,6 +132,7 @@ def lib():
         "amdp_schedule_generate": (C.c_int, [P(amdp_sched_params_t), P(amdp_event_t), sz, P(sz)]),
         "amdp_schedule_stats": (C.c_int, [P(amdp_event_t), sz, i32, P(amdp_sched_stats_t)]),
         "amdp_stage_map": (C.c_int, [i32, i32, i32, P(i32)]),
+        "amdp_schedule_preset": (C.c_int, [i32, i32, i32, i32, i32, P(amdp_sched_params_t)]),
         "amdp_system_simulate": (C.c_int, [P(amdp_sim_params_t), P(amdp_sim_op_t), sz, P(sz), P(C.c_int64),
                                            P(amdp_sim_result_t)]),
         "amdp_stage_n_params": (sz, [P(amdp_stage_config_t)]),
@@ -162,7 +163,7 @@ def lib():
     return L
 
 
-EXPORTED = ["amdp_strerror", "amdp_last_hip_error", "amdp_schedule_generate", "amdp_schedule_stats", "amdp_stage_map",
+EXPORTED = ["amdp_strerror", "amdp_last_hip_error", "amdp_schedule_generate", "amdp_schedule_stats", "amdp_stage_map", "amdp_schedule_preset",
             "amdp_system_simulate",
             "amdp_stage_n_params", "amdp_stage_workspace_bytes", "amdp_stage_param_layout",
             "amdp_stage_create", "amdp_stage_destroy", "amdp_stage_set_state", "amdp_stage_get_state",
@@ -193,6 +194,20 @@ def amdp_schedule_generate(depth, pipelines, stage, threshold, n_minibatches, in
     arr = (amdp_event_t * max(1, n.value))()
     _check(lib().amdp_schedule_generate(C.byref(p), arr, n.value, C.byref(n)), "amdp_schedule_generate")
     return (amdp_event_t * n.value).from_buffer(arr) if n.value else (amdp_event_t * 0)()
+
+
+PRESET_AMDP, PRESET_PIPEDREAM, PRESET_PIPEDREAM_2BW, PRESET_SYNC_1F1B = 0, 1, 2, 3
+U_FLUSH = 2
+
+
+def amdp_schedule_preset(preset, depth, stage, n_minibatches, microbatches=0):
+    """Events of one of Table 1's schedules for one stage, and the window length used."""
+    p = amdp_sched_params_t()
+    _check(lib().amdp_schedule_preset(preset, depth, stage, n_minibatches, microbatches, C.byref(p)),
+           "amdp_schedule_preset")
+    ev = amdp_schedule_generate(p.depth, p.pipelines, p.stage, p.threshold, p.n_minibatches, p.inject_limit,
+                                p.update_placement, p.bwd_version)
+    return ev, p
 
 
 def amdp_schedule_stats(events, threshold):

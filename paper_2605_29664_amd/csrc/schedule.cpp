@@ -22,7 +22,8 @@ extern "C" int amdp_schedule_generate(const amdp_sched_params_t* p, amdp_event_t
     const int d = p->depth, P = p->pipelines, i = p->stage, n = p->inject_limit;
     const int T = p->threshold, M = p->n_minibatches;
     if (d < 1 || P < 1 || P > 256 || i < 0 || i >= d || n < 1 || T < 1 || M < 0) return AMDP_E_INVAL;
-    if (p->update_placement != AMDP_U_NEXT_BUBBLE && p->update_placement != AMDP_U_EAGER)
+    if (p->update_placement != AMDP_U_NEXT_BUBBLE && p->update_placement != AMDP_U_EAGER &&
+        p->update_placement != AMDP_U_FLUSH)
         return AMDP_E_INVAL;
     if (p->bwd_version != AMDP_BWD_STASHED && p->bwd_version != AMDP_BWD_CURRENT) return AMDP_E_INVAL;
 
@@ -33,8 +34,8 @@ extern "C" int amdp_schedule_generate(const amdp_sched_params_t* p, amdp_event_t
     if (!total) return AMDP_OK;
 
     const int w = std::min(n, d - i);          // warm-up forwards per pipeline (Section 3.1)
-    const int rounds = ceil_div(M, P);
-    const bool eager = p->update_placement == AMDP_U_EAGER;
+    const bool flush = p->update_placement == AMDP_U_FLUSH;
+    const bool eager = p->update_placement == AMDP_U_EAGER || flush;
     const bool stashed = p->bwd_version == AMDP_BWD_STASHED;
 
     std::vector<uint32_t> fwd_tag((size_t)M, 0);
@@ -54,27 +55,38 @@ extern "C" int amdp_schedule_generate(const amdp_sched_params_t* p, amdp_event_t
         const bool partial = (long long)(window + 1) * T > M;
         emit(AMDP_EV_U, 0, partial ? AMDP_FLAG_PARTIAL_WINDOW : 0, window, applied);
     };
-    auto forward_round = [&](int g) {
-        for (int m = g * P; m < std::min((g + 1) * P, M); ++m) {
-            fwd_tag[m] = applied;
-            emit(AMDP_EV_F, m % P, 0, m, applied);
+    // 1F1B per replica over minibatches [first, last): w forward rounds, then
+    // backward round g / forward round g + w.
+    auto one_f_one_b = [&](int first, int last) {
+        const int rounds = ceil_div(last - first, P);
+        auto forward_round = [&](int g) {
+            for (int m = first + g * P; m < std::min(first + (g + 1) * P, last); ++m) {
+                fwd_tag[m] = applied;
+                emit(AMDP_EV_F, m % P, 0, m, applied);
+            }
+        };
+        auto backward_round = [&](int g) {
+            for (int m = first + g * P; m < std::min(first + (g + 1) * P, last); ++m) {
+                // "next bubble": the update of the window that just closed goes in
+                // front of the first backward of the following window
+                if (!eager && m > 0 && m % T == 0) emit_update(m / T - 1);
+                emit(AMDP_EV_B, m % P, 0, m, stashed ? fwd_tag[m] : applied);
+                emit(AMDP_EV_A, m % P, 0, m, 0);
+                if (eager && ((m + 1) % T == 0 || (flush && m == M - 1))) emit_update(m / T);
+            }
+        };
+        for (int g = 0; g < std::min(w, rounds); ++g) forward_round(g);
+        for (int g = 0; g < rounds; ++g) {
+            backward_round(g);
+            if (g + w < rounds) forward_round(g + w);
         }
     };
-    auto backward_round = [&](int g) {
-        for (int m = g * P; m < std::min((g + 1) * P, M); ++m) {
-            // "next bubble": the update of the window that just closed goes in
-            // front of the first backward of the following window
-            if (!eager && m > 0 && m % T == 0) emit_update(m / T - 1);
-            emit(AMDP_EV_B, m % P, 0, m, stashed ? fwd_tag[m] : applied);
-            emit(AMDP_EV_A, m % P, 0, m, 0);
-            if (eager && (m + 1) % T == 0) emit_update(m / T);
-        }
-    };
-
-    for (int g = 0; g < std::min(w, rounds); ++g) forward_round(g);
-    for (int g = 0; g < rounds; ++g) {
-        backward_round(g);
-        if (g + w < rounds) forward_round(g + w);
+    if (flush) {
+        // synchronous schedule: drain a window and apply its update before the
+        // next window's first forward
+        for (int first = 0; first < M; first += T) one_f_one_b(first, std::min(first + T, M));
+    } else {
+        one_f_one_b(0, M);
     }
     while ((int)applied < n_updates) emit_update((int)applied);   // closes the last window
 
@@ -160,6 +172,47 @@ extern "C" int amdp_stage_map(int32_t depth, int32_t pipeline, int32_t stage, in
     int g = (j % 2 == 0) ? (2 * j + i) % d : (2 * j - i + d + 1) % d;
     *gpu_out = ((g % d) + d) % d;
     return AMDP_OK;
+}
+
+extern "C" int amdp_schedule_preset(int32_t preset, int32_t depth, int32_t stage, int32_t n_minibatches,
+                                    int32_t microbatches, amdp_sched_params_t* out) {
+    if (!out || depth < 1 || stage < 0 || stage >= depth || n_minibatches < 0) return AMDP_E_INVAL;
+    std::memset(out, 0, sizeof(*out));
+    out->struct_size = sizeof(*out);
+    out->depth = depth;
+    out->stage = stage;
+    out->n_minibatches = n_minibatches;
+    out->pipelines = 1;
+    switch (preset) {
+        case AMDP_PRESET_AMDP:             // n = 2, d/2 pipelines, window >= d, update in the next bubble
+            out->pipelines = std::max(1, depth / 2);
+            out->inject_limit = 2;
+            out->threshold = microbatches > 0 ? microbatches : 2 * depth;
+            out->update_placement = AMDP_U_NEXT_BUBBLE;
+            out->bwd_version = AMDP_BWD_CURRENT;
+            return AMDP_OK;
+        case AMDP_PRESET_PIPEDREAM:        // d minibatches in flight, update after every backward, weight stashing
+            out->inject_limit = depth;
+            out->threshold = 1;
+            out->update_placement = AMDP_U_EAGER;
+            out->bwd_version = AMDP_BWD_STASHED;
+            return AMDP_OK;
+        case AMDP_PRESET_PIPEDREAM_2BW:    // d in flight, gradients coalesced over d minibatches, double-buffered weights
+            out->inject_limit = depth;
+            out->threshold = microbatches > 0 ? microbatches : depth;
+            if (out->threshold < depth) return AMDP_E_INVAL;
+            out->update_placement = AMDP_U_EAGER;
+            out->bwd_version = AMDP_BWD_STASHED;
+            return AMDP_OK;
+        case AMDP_PRESET_SYNC_1F1B:        // one minibatch of `microbatches` microbatches, flushed
+            if (microbatches < 1) return AMDP_E_INVAL;
+            out->inject_limit = depth;
+            out->threshold = microbatches;
+            out->update_placement = AMDP_U_FLUSH;
+            out->bwd_version = AMDP_BWD_STASHED;
+            return AMDP_OK;
+    }
+    return AMDP_E_INVAL;
 }
 
 namespace {

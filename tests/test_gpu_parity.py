@@ -335,6 +335,21 @@ def test_tied_embedding_gradients_are_summed_into_both_stages():
     last.stage.close()
 
 
+@pytest.mark.parametrize("name,kw", [
+    ("pipedream", dict(inject_limit=4, threshold=1, placement=OSched.EAGER, policy=OSched.STASHED)),
+    ("pipedream_2bw", dict(inject_limit=4, threshold=4, placement=OSched.EAGER, policy=OSched.STASHED)),
+    ("sync_1f1b", dict(inject_limit=4, threshold=6, placement=OSched.FLUSH, policy=OSched.STASHED)),
+])
+def test_comparison_schedules_through_the_stage_library(name, kw):
+    """The schedules Table 1 compares AMDP with, run through the same stage
+    library: PipeDream's stage 1 of 4 stashes three versions, 2BW two, the
+    flushed schedule none."""
+    w = W.TINY["gpt_tile"].with_(depth=4, pipelines=1, stage=1, n_layers=1, lr=1e-3)
+    rep = run_parity(w, n_minibatches=14, verbose=False, **kw)
+    _report(name, rep)
+    assert rep["ok"], worst_entries(rep)
+
+
 def test_hip_graph_replay_matches_eager():
     """Forward + backward + accumulate captured once in a HIP graph (the library
     clears and copies with its own kernels and forks / joins its side stream

@@ -42,12 +42,12 @@ def test_generator_equals_oracle_over_grid():
                 for T in sorted({1, 2, P, 2 * P, d, 2 * d + 1, 4 * d}):
                     for M in sorted({0, 1, T, 3 * T + 1, 5 * T - 1}):
                         for n_inj in (1, 2, 3):
-                            for pl, pol in itertools.product((0, 1), (0, 1)):
+                            for pl, pol in itertools.product((0, 1, 2), (0, 1)):
                                 mine = amdp.amdp_schedule_generate(d, P, i, T, M, n_inj, pl, pol)
                                 ref = S.generate(d, P, i, T, M, n_inj, pl, pol)
                                 assert _as_tuples(mine) == [tuple(e) for e in ref], (d, P, i, T, M, n_inj, pl, pol)
                                 n += 1
-    assert n > 10000
+    assert n > 15000
 
 
 def test_generator_benchmark_configs_and_stats(golden_dir):
@@ -191,3 +191,31 @@ def test_system_simulation_rejects_bad_parameters():
                 (4, 2, 1, 1, 0, 2, 0), (4, 2, 1, 1, 1, 0, 0), (4, 2, 1, 1, 1, 2, -1)]:
         with pytest.raises(amdp.AmdpError):
             amdp.amdp_system_simulate(*bad)
+
+
+def test_comparison_schedule_presets():
+    """amdp_schedule_preset fills the generator settings of the schedules that
+    Table 1 compares; the events equal the oracle's for those settings and
+    show the table's weight-version counts."""
+    for d in (2, 4, 8):
+        M = 6 * d
+        for i in range(d):
+            ev, p = amdp.amdp_schedule_preset(amdp.PRESET_PIPEDREAM, d, i, M)
+            assert (p.pipelines, p.inject_limit, p.threshold, p.update_placement, p.bwd_version) == (1, d, 1, 1, 0)
+            assert _as_tuples(ev) == [tuple(e) for e in S.generate(d, 1, i, 1, M, d, S.EAGER, S.STASHED)]
+            assert amdp.amdp_schedule_stats(ev, 1)["max_live_versions"] == d - i
+            ev, p = amdp.amdp_schedule_preset(amdp.PRESET_PIPEDREAM_2BW, d, i, M)
+            assert _as_tuples(ev) == [tuple(e) for e in S.generate(d, 1, i, d, M, d, S.EAGER, S.STASHED)]
+            assert amdp.amdp_schedule_stats(ev, d)["max_live_versions"] <= 2
+            ev, p = amdp.amdp_schedule_preset(amdp.PRESET_SYNC_1F1B, d, i, M, microbatches=2 * d)
+            assert _as_tuples(ev) == [tuple(e) for e in S.generate(d, 1, i, 2 * d, M, d, S.FLUSH, S.STASHED)]
+            st = amdp.amdp_schedule_stats(ev, 2 * d)
+            assert st["max_mismatch"] == 0 and st["max_live_versions"] == 1
+            ev, p = amdp.amdp_schedule_preset(amdp.PRESET_AMDP, d, i, M)
+            assert (p.pipelines, p.inject_limit, p.threshold) == (max(1, d // 2), 2, 2 * d)
+            assert _as_tuples(ev) == [tuple(e) for e in S.generate(d, max(1, d // 2), i, 2 * d, M, 2, S.NEXT_BUBBLE, S.CURRENT)]
+            assert amdp.amdp_schedule_stats(ev, 2 * d)["max_mismatch"] <= 1
+    with pytest.raises(amdp.AmdpError):
+        amdp.amdp_schedule_preset(amdp.PRESET_SYNC_1F1B, 4, 0, 8)          # needs the microbatch count
+    with pytest.raises(amdp.AmdpError):
+        amdp.amdp_schedule_preset(7, 4, 0, 8)

@@ -219,3 +219,46 @@ def test_three_stashed_versions_reachable():
     ev = S.generate(16, 4, 8, 4, 64, inject_limit=3)
     st = S.stats(ev, 4)
     assert st["max_live_versions"] == 4 and st["max_mismatch"] == 3
+
+
+# ---------------------------------------------------------------- comparison schedules of Table 1
+@pytest.mark.parametrize("d,T,M", [(4, 4, 12), (4, 6, 15), (8, 8, 16), (6, 3, 7)])
+def test_flushed_schedule_is_synchronous(d, T, M):
+    """FLUSH placement: every window is a complete 1F1B schedule of its own
+    followed by its update, so no minibatch sees an update between its forward
+    and backward, one version is live, and the events of window u are exactly
+    the events of a stand-alone schedule of its minibatches shifted by u*T."""
+    for i in range(d):
+        ev = S.generate(d, 1, i, T, M, inject_limit=d, placement=S.FLUSH)
+        st = S.stats(ev, T)
+        assert st["max_mismatch"] == 0 and st["max_live_versions"] == 1
+        assert st["max_inflight"] == min(d - i, T, M)
+        assert all(e.version == e.mb // T for e in ev if e.kind in (S.F, S.B))
+        pos = 0
+        for u in range(-(-M // T)):
+            size = min(T, M - u * T)
+            alone = S.generate(d, 1, i, size, size, inject_limit=d, placement=S.EAGER)
+            chunk = ev[pos:pos + len(alone)]
+            assert [(e.kind, e.mb) for e in chunk if e.kind != S.U] == \
+                   [(e.kind, e.mb + u * T) for e in alone if e.kind != S.U]
+            assert chunk[-1].kind == S.U and chunk[-1].mb == u
+            pos += len(alone)
+        assert pos == len(ev)
+
+
+@pytest.mark.parametrize("d", [2, 4, 8])
+def test_weight_versions_of_the_asynchronous_comparison_schedules(d):
+    """Table 1's weight-memory column: PipeDream keeps between one and d weight
+    versions (d - i at stage i: one per minibatch in flight), PipeDream-2BW two,
+    AMDP one besides the current (its backward uses the current weights and is
+    off by at most one update, Lemma 1)."""
+    M = 6 * d
+    for i in range(d):
+        pd = S.generate(d, 1, i, 1, M, inject_limit=d, placement=S.EAGER, bwd_version=S.STASHED)
+        assert S.stats(pd, 1)["max_live_versions"] == d - i
+        assert S.stats(pd, 1)["max_mismatch"] == d - i - 1            # what stashing hides from backward
+        bw = S.generate(d, 1, i, d, M, inject_limit=d, placement=S.EAGER, bwd_version=S.STASHED)
+        assert S.stats(bw, d)["max_live_versions"] == (2 if i < d - 1 else 1)
+        am = S.generate(d, max(1, d // 2), i, 2 * d, M, inject_limit=2, placement=S.NEXT_BUBBLE,
+                        bwd_version=S.CURRENT)
+        assert S.stats(am, 2 * d)["max_mismatch"] <= 1
