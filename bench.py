@@ -143,6 +143,7 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    cursor = n_warm + K          # next step of the schedule (steps must be run in order)
     tokens = K * T * w.tokens
     value = tokens / elapsed
     flops_step = T * algorithmic_flops_per_minibatch(w)
@@ -184,7 +185,8 @@ def main():
                     "avg_launch_ms": r["ms"] / r["launches"], "flops_per_launch": r["flops"] / r["launches"]}
 
         # (a) as timed: gradient leaves overlap with the dX chain on the side stream
-        prof = profile_step(steps[n_warm + K])
+        prof = profile_step(steps[cursor])
+        cursor += 1
         table = {}
         for name, r in sorted(prof.items(), key=lambda kv: -kv[1]["ms"]):
             row = {"launches": r["launches"], "ms": round(r["ms"], 4)}
@@ -211,9 +213,10 @@ def main():
         result["streaming_as_timed"] = streaming(prof)
         result["streaming"] = result["streaming_as_timed"]
         # (b) every kernel alone on the GPU (side stream off), same launches
-        if len(steps) > n_warm + K + 1:
+        if len(steps) > cursor:
             stage.amdp_stage_set_overlap(False)
-            iso = profile_step(steps[n_warm + K + 1])
+            iso = profile_step(steps[cursor])
+            cursor += 1
             stage.amdp_stage_set_overlap(True)
             result["roofline_isolated"] = dominant_gemm(iso)
             result["streaming"] = streaming(iso)
@@ -229,12 +232,11 @@ def main():
 
     # ---- the same steps with the accumulation fused into backward (an option of
     # the library; `value` above is the schedule's own order) --------------------
-    if not args.fused_accumulate and len(steps) >= n_warm + 2 * K + 2:
+    if not args.fused_accumulate and len(steps) >= cursor + K:
         stage.amdp_stage_set_fused_accumulate(True)
-        first = n_warm + K + 2
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for i in range(first, first + K):
+        for i in range(cursor, cursor + K):
             run_step(steps[i])
         torch.cuda.synchronize()
         el = time.perf_counter() - t0
