@@ -31,6 +31,12 @@ __device__ __forceinline__ int tile_pos(int row) { return (row & ~15) | ((row & 
 
 constexpr float LOG2E = 1.4426950408889634f;
 
+// 2^x as the bare hardware instruction. The library exp2f wraps it in a range
+// test and a rescale for results below the normal range (four more vector
+// instructions per call); here x <= 0 always and a result that small is a
+// probability that rounds to zero in bf16 anyway.
+__device__ __forceinline__ float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }
+
 __device__ __forceinline__ bf16x8 pack8(const f32x16& p, int first) {
     bf16x8 out;
 #pragma unroll
@@ -188,12 +194,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const float p = exp2f(fmaf(st[kt][v], scale_log2e, -m_use));
+                const float p = exp2_raw(fmaf(st[kt][v], scale_log2e, -m_use));
                 st[kt][v] = p;
                 lsum += p;
             }
         if (m_new != m_run) {          // most blocks leave the running maximum alone
-            const float alpha = exp2f(m_run - m_use);
+            const float alpha = exp2_raw(m_run - m_use);
             l_run *= alpha;
 #pragma unroll
             for (int t = 0; t < DT; ++t)
@@ -282,7 +288,7 @@ __device__ __forceinline__ void store_headrow(bf16* row, const f32x16 (&acc)[4],
 // dK, dV. Same grid; each wave owns 32 keys (lane % 32) and walks the
 // query tiles of 64 that can see them. dqkv: [b*s, 3D], K block at +D, V at +2D.
 template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 2 : 1))) void flash_bwd_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                             const float* __restrict__ lse2,
                                                             const float* __restrict__ delta, bf16* __restrict__ dqkv,
                                                             const int32_t* __restrict__ valid_len, int s, int H,
@@ -356,7 +362,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16* __restri
                 for (int e = 0; e < 4; ++e) {
                     const int v = 4 * gq + e;
                     const int q = q0 + qt * 32 + 8 * gq + 4 * half + e;
-                    float p = exp2f(fmaf(sc[v], sl2, -l4[e]));
+                    float p = exp2_raw(fmaf(sc[v], sl2, -l4[e]));
                     if ((CAUSAL && key > q) || key_dead) p = 0.f;
                     sc[v] = p;
                     dp[v] = p * (dp[v] - d4[e]);         // the factor `scale` of dS is applied to dK at the end
@@ -444,7 +450,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int key = k0 + kt * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                float p = exp2f(fmaf(sc[v], sl2, -lse_q));
+                float p = exp2_raw(fmaf(sc[v], sl2, -lse_q));
                 if ((CAUSAL && key > q) || (!CAUSAL && key >= klimit)) p = 0.f;   // causal stages carry no padding mask
                 dp[v] = p * (dp[v] - delta_q);           // the factor `scale` of dS is applied to dQ at the end
             }
