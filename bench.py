@@ -56,7 +56,7 @@ def recorded_traffic(workload, kernel):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=str, default="2", help="benchmark configuration 1..5 or a test shape name")
     ap.add_argument("--no-cpu-baseline", action="store_true")
