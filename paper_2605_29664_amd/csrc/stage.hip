@@ -333,9 +333,10 @@ hipError_t launch_tile(amdp_stage* st, const GemmArgs& g) {
                       : launch_gemm_mfma_inst<BM, BN, A_KM, B_KM, false, WGN>(g, st->launch);
 }
 
-// Tile choice, from measurement on MI355X: the largest tile that still gives
-// at least 192 workgroups (three quarters of the compute units) wins; when no
-// tile gets there, the one with the most workgroups does.
+// Tile choice, from measurement on MI355X: the largest tile that still fills
+// the GPU wins (the 256x256 tile needs a workgroup for every compute unit, the
+// smaller ones three quarters of them); when no tile gets there, the one with
+// the most workgroups does.
 template <bool A_KM, bool B_KM>
 int gemm_bf16_layout(amdp_stage* st, const GemmArgs& g) {
     struct Cand { int bm, bn; bool ok; };
@@ -345,7 +346,7 @@ int gemm_bf16_layout(amdp_stage* st, const GemmArgs& g) {
     auto tiles = [&](const Cand& c) { return (long)(g.M / c.bm) * (g.N / c.bn) * g.batch; };
     int pick = -1;
     for (int i = 0; i < 5 && pick < 0; ++i)
-        if (cand[i].ok && tiles(cand[i]) >= 192) pick = i;
+        if (cand[i].ok && tiles(cand[i]) >= (i == 0 ? st->n_cu : st->n_cu * 3 / 4)) pick = i;
     if (pick < 0)
         for (int i = 0; i < 5; ++i)
             if (cand[i].ok && (pick < 0 || tiles(cand[i]) > tiles(cand[pick]))) pick = i;
@@ -365,10 +366,10 @@ int gemm_bf16_layout(amdp_stage* st, const GemmArgs& g) {
     switch (pick) {
         case 0: e = launch_tile<256, 256, A_KM, B_KM, 4>(st, g); break;   // eight waves (two per SIMD), each 128x64 of the tile
         case 1:
-            // up to one workgroup per compute unit: eight waves (two per SIMD, each
-            // 64x32 of the tile) hide latency that a second resident workgroup would
-            // otherwise hide; measured 9-14 % faster there, 2-5 % slower beyond
-            e = tiles(cand[1]) <= st->n_cu ? launch_tile<128, 128, A_KM, B_KM, 4>(st, g)
+            // up to three workgroups per compute unit: eight waves (two per SIMD, each
+            // 64x32 of the tile) hide the latency that further resident workgroups
+            // would otherwise hide; measured 3-14 % faster there, 2-5 % slower beyond
+            e = tiles(cand[1]) <= 3 * st->n_cu ? launch_tile<128, 128, A_KM, B_KM, 4>(st, g)
                                            : launch_tile<128, 128, A_KM, B_KM>(st, g);
             break;
         case 2: e = launch_tile<128, 64, A_KM, B_KM>(st, g); break;
