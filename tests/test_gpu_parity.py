@@ -22,7 +22,7 @@ def _report(name, rep):
 
 @pytest.fixture(autouse=True)
 def _clean_env():
-    saved = {k: os.environ.get(k) for k in ("AMDP_GEMM_TR", "AMDP_GEMM_TILE", "AMDP_FLASH")}
+    saved = {k: os.environ.get(k) for k in ("AMDP_GEMM_TR", "AMDP_GEMM_TILE", "AMDP_FLASH", "AMDP_GEMM_DIRECT")}
     yield
     for k, v in saved.items():
         if v is None:
@@ -77,11 +77,14 @@ def test_tile_bf16_head_dim_128(key):
     assert rep["ok"], worst_entries(rep)
 
 
+@pytest.mark.parametrize("direct", ["1", "0"])
 @pytest.mark.parametrize("tile", ["256", "128", "128064", "64128", "64"])
-def test_tile_bf16_forced_tile(tile):
+def test_tile_bf16_forced_tile(tile, direct):
     """Every matrix-core tile shape on the same workload (a tile that does not
-    divide a product's shape leaves that product to the default choice)."""
+    divide a product's shape leaves that product to the default choice), with
+    the NT products loading their tiles straight into LDS and through registers."""
     os.environ["AMDP_GEMM_TILE"] = tile
+    os.environ["AMDP_GEMM_DIRECT"] = direct
     rep = run_parity(W.TINY["gpt_tile"], n_windows=1, verbose=False)
     _report(f"gpt_tile_forced_{tile}", rep)
     assert rep["ok"], worst_entries(rep)
