@@ -1,16 +1,24 @@
-// NT GEMM (both operands k-contiguous: dX = dY W^T, logits = z E^T) with tiles
-// loaded from global memory STRAIGHT INTO LDS (global_load_lds_dwordx4): no
-// staging registers, no LDS-write instructions, and the data of a tile is in
-// flight for a whole k-tile of matrix work.
+// bf16 GEMM on the matrix cores with tiles loaded from global memory STRAIGHT
+// INTO LDS (global_load_lds_dwordx4): no staging registers, no LDS-write
+// instructions, and the data of a tile is in flight for a whole k-tile of
+// matrix work. Same tiling, fragment double buffering, XCD-aware tile order and
+// epilogue as gemm_mfma_kernel; plain problems only (no batch, no causal band).
+// Measured on MI355X: 4-10 % faster than the register-staged kernel when both
+// operands are k-contiguous (NT) and more than one workgroup per compute unit
+// is resident; slower (up to 20 % at the 256x256 tile) when an operand is
+// m/n-contiguous, so the stage only uses it for NT products.
 //
 // One such load moves 64 lanes x 16 bytes = 1 KB to consecutive LDS addresses
 // (lane l's 16 bytes land at base + 16 l), so a tile row cannot be padded.
-// A [rows][64 k] bf16 tile is 128 bytes per row = 8 chunks of 16 bytes; chunk c
-// of row r is stored at chunk position c ^ ((r >> 1) & 7). A 128-bit fragment
-// read by 16 consecutive rows of one chunk then touches all 64 banks once. The
-// swizzle costs nothing at load time (the lane that writes position p of row r
-// simply fetches chunk p ^ ((r >> 1) & 7) from memory) and four precomputed
-// lane offsets per operand at read time (one per k-step).
+// Bank conflicts are avoided by a swizzle instead, which costs nothing at load
+// time (a lane simply fetches the piece of memory that belongs at the LDS
+// position it writes) and a few precomputed lane offsets at read time:
+//   * k-contiguous operand, tile [rows][64 k], 128 bytes per row = 8 chunks of
+//     16 bytes: chunk c of row r sits at chunk position c ^ ((r >> 1) & 7); a
+//     128-bit fragment read by 16 consecutive rows touches all 64 banks once;
+//   * m/n-contiguous operand, tile [64 k][R], R*2 bytes per row: the 64-byte
+//     block b of row k sits at block position b ^ (k & 3); the transposing read
+//     of half a wave (4 consecutive k, 64 bytes each) touches all banks once.
 #pragma once
 #include "gemm_mfma.h"
 
@@ -18,15 +26,73 @@ namespace amdp {
 
 typedef __attribute__((address_space(3))) void lds_void;
 
-template <int BM, int BN, int WGN>
-__global__ __launch_bounds__(128 * WGN) void gemm_mfma_nt_dl_kernel(GemmArgs g) {
+// One operand's tile: R rows (m or n) by 64 k. NW = waves in the workgroup.
+template <int R, bool KM, int NW>
+struct DlTile {
+    static constexpr int BYTES = R * MF_BK * 2;
+    static constexpr int ROWB = KM ? R * 2 : MF_BK * 2;       // bytes per LDS row
+    static constexpr int CHUNK_ROWS = 1024 / ROWB;            // LDS rows per 1 KB load
+    static constexpr int PW = BYTES / 1024 / NW;              // loads per wave
+    static_assert(BYTES % (1024 * NW) == 0, "tile must split into whole 1 KB loads per wave");
+    static_assert(NW % 2 == 0 && (!KM || R == 128 || R == 256), "swizzle terms assume these shapes");
+
+    // Byte offset from the tile's first element (row 0, k 0) of what this lane
+    // fetches in pass 0; rs = elements between consecutive m/n rows, ks =
+    // elements between consecutive k.
+    __device__ static __forceinline__ long lane_goff(int wave, int lane, long rs, long ks) {
+        if constexpr (!KM) {
+            const int row = 8 * wave + (lane >> 3), pos = lane & 7;
+            const int f = (row >> 1) & 7;
+            return (long)row * rs * 2 + ((pos ^ f) * 16);
+        } else {
+            const int o = 16 * lane;                          // LDS byte inside the 1 KB chunk
+            const int krow = CHUNK_ROWS * wave + o / ROWB, pb = o % ROWB;
+            const int b = (((pb >> 6) ^ (krow & 3)) << 6) | (pb & 63);
+            return (long)krow * ks * 2 + b;
+        }
+    }
+    // pass p adds p * pass_gstride (the swizzle terms do not change with the pass)
+    __device__ static __forceinline__ long pass_gstride(long rs, long ks) {
+        return KM ? (long)CHUNK_ROWS * NW * ks * 2 : (long)8 * NW * rs * 2;
+    }
+    __device__ static __forceinline__ long ktile_gstride(long ks) { return KM ? (long)MF_BK * ks * 2 : MF_BK * 2; }
+
+    // Fragment addressing. `origin` = first row of the wave's part of the tile.
+    // !KM: index = k-step (4 lane offsets), sub-tile j is an immediate.
+    //  KM: index = sub-tile (up to 4 lane offsets), k-step is an immediate.
+    __device__ static __forceinline__ int frag_off(int origin, int lane, int idx) {
+        if constexpr (!KM) {
+            const int r = lane & 31, f = (r >> 1) & 7, half = lane >> 5;
+            return (origin + r) * ROWB + (((2 * idx + half) ^ f) * 16);
+        } else {
+            const int q = lane >> 4, i = lane & 15;
+            const int krow = 8 * (q >> 1) + (i >> 2), sx = (i >> 2) & 3;
+            const int blk = (origin + 32 * idx) * 2 / 64;
+            return krow * ROWB + ((blk ^ sx) << 6) + (16 * (q & 1) + 4 * (i & 3)) * 2;
+        }
+    }
+    // f[] = lds + operand base + frag_off(origin, lane, 0..3)
+    __device__ static __forceinline__ bf16x8 frag(lds_u8* const (&f)[4], int stage, int j, int kk) {
+        if constexpr (!KM) {
+            return *(lds_bf16x8*)(f[kk] + stage + j * 32 * ROWB);
+        } else {
+            lds_u8* p = f[j] + stage + kk * 16 * ROWB;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * ROWB));
+            typedef __attribute__((ext_vector_type(8))) short s16x8;
+            return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+    }
+};
+
+template <int BM, int BN, bool A_KM, bool B_KM, int WGN>
+__global__ __launch_bounds__(128 * WGN) void gemm_mfma_dl_kernel(GemmArgs g) {
     constexpr int NT = 128 * WGN, NW = NT / 64;
     constexpr int WM = BM / 2, WN = BN / WGN;
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int ROWB = MF_BK * 2;                       // 128 bytes per tile row
-    constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE = A_BYTES + B_BYTES;
-    constexpr int A_PW = BM / 8 / NW, B_PW = BN / 8 / NW; // 1 KB chunk loads per wave and operand
-    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split into whole chunk loads per wave");
+    using TA = DlTile<BM, A_KM, NW>;
+    using TB = DlTile<BN, B_KM, NW>;
+    constexpr int STAGE = TA::BYTES + TB::BYTES;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     lds_u8* lds = (lds_u8*)smem_raw;
 
@@ -45,32 +111,28 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_nt_dl_kernel(GemmArgs g) 
     const int pn = (pid % per_group) / gsize;
     const int m0 = pm * BM, n0 = pn * BN;
 
-    // ---- what this lane fetches: row 8*(wave + NW*p) + lane/8 of the tile, LDS chunk position lane%8
-    const int rowl = lane >> 3, pos = lane & 7;
-    const int fl = (4 * (wave & 1) + (rowl >> 1)) & 7;    // (row >> 1) & 7; NW is even, so the pass does not change it
-    const char* pa = (const char*)((const bf16*)g.A + (long)(m0 + 8 * wave + rowl) * g.a_rs) + ((pos ^ fl) * 16);
-    const char* pb = (const char*)((const bf16*)g.B + (long)(n0 + 8 * wave + rowl) * g.b_cs) + ((pos ^ fl) * 16);
-    const long a_pass = (long)8 * NW * g.a_rs * 2, b_pass = (long)8 * NW * g.b_cs * 2;
+    const char* pa = (const char*)((const bf16*)g.A + (long)m0 * g.a_rs) + TA::lane_goff(wave, lane, g.a_rs, g.a_cs);
+    const char* pb = (const char*)((const bf16*)g.B + (long)n0 * g.b_cs) + TB::lane_goff(wave, lane, g.b_cs, g.b_rs);
+    const long a_pass = TA::pass_gstride(g.a_rs, g.a_cs), b_pass = TB::pass_gstride(g.b_cs, g.b_rs);
+    const long a_step = TA::ktile_gstride(g.a_cs), b_step = TB::ktile_gstride(g.b_rs);
     auto issue_tile = [&](int stage) {
 #pragma unroll
-        for (int p = 0; p < A_PW; ++p)
+        for (int p = 0; p < TA::PW; ++p)
             __builtin_amdgcn_global_load_lds(pa + p * a_pass, (lds_void*)(lds + stage + (wave + NW * p) * 1024), 16, 0, 0);
 #pragma unroll
-        for (int p = 0; p < B_PW; ++p)
-            __builtin_amdgcn_global_load_lds(pb + p * b_pass, (lds_void*)(lds + stage + A_BYTES + (wave + NW * p) * 1024), 16, 0, 0);
-        pa += MF_BK * 2;
-        pb += MF_BK * 2;
+        for (int p = 0; p < TB::PW; ++p)
+            __builtin_amdgcn_global_load_lds(pb + p * b_pass,
+                                             (lds_void*)(lds + stage + TA::BYTES + (wave + NW * p) * 1024), 16, 0, 0);
+        pa += a_step;
+        pb += b_step;
     };
 
-    // ---- where this lane reads fragments: row lane%32 of a 32-row group, chunk 2*kk + lane/32
-    const int fr = ((lane & 31) >> 1) & 7, half = lane >> 5;
     lds_u8* fa[4];
     lds_u8* fb[4];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        const int off = (lane & 31) * ROWB + (((2 * kk + half) ^ fr) * 16);
-        fa[kk] = lds + (wm * WM) * ROWB + off;
-        fb[kk] = lds + A_BYTES + (wn * WN) * ROWB + off;
+    for (int x = 0; x < 4; ++x) {
+        fa[x] = lds + TA::frag_off(wm * WM, lane, x);
+        fb[x] = lds + TA::BYTES + TB::frag_off(wn * WN, lane, x);
     }
 
     f32x16 acc[TM][TN];
@@ -82,14 +144,14 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_nt_dl_kernel(GemmArgs g) 
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     const int nk = g.K / MF_BK;
-    constexpr int NDS = TM + TN, NMF = TM * TN, NVM = A_PW + B_PW;
+    constexpr int NDS = TM * (A_KM ? 2 : 1) + TN * (B_KM ? 2 : 1), NMF = TM * TN, NVM = TA::PW + TB::PW;
 
     bf16x8 va[2][TM], vb[2][TN];
     auto load_frags = [&](int buf, int stage, int kk) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) va[buf][i] = *(lds_bf16x8*)(fa[kk] + stage + i * 32 * ROWB);
+        for (int i = 0; i < TM; ++i) va[buf][i] = TA::frag(fa, stage, i, kk);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) vb[buf][j] = *(lds_bf16x8*)(fb[kk] + stage + j * 32 * ROWB);
+        for (int j = 0; j < TN; ++j) vb[buf][j] = TB::frag(fb, stage, j, kk);
     };
     auto mfma_step = [&](int buf) {
 #pragma unroll
@@ -107,13 +169,16 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_nt_dl_kernel(GemmArgs g) 
         if (NDS > NMF) __builtin_amdgcn_sched_group_barrier(0x100, NDS - NMF, 0);
     };
 
-    // tiles 0 and 1 travel; tile kt+2 is issued at the barrier inside iteration kt,
-    // when every wave is done with the stage it goes to
+    // Tiles 0 and 1 travel first; tile kt+2 is issued at the barrier inside
+    // iteration kt, when every wave is done with the stage it goes to.
+    // s_waitcnt immediate: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8.
     if (nk > 0) issue_tile(0);
-    if (nk > 1) issue_tile(STAGE);
-    // s_waitcnt immediate: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8
-    if (nk > 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (NVM & 15) | ((NVM >> 4) << 14));   // vmcnt(NVM): tile 0 has landed
-    else __builtin_amdgcn_s_waitcnt(0x0F70);                                           // vmcnt(0)
+    if (nk > 1) {
+        issue_tile(STAGE);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (NVM & 15) | ((NVM >> 4) << 14));   // vmcnt(NVM): tile 0 has landed
+    } else {
+        __builtin_amdgcn_s_waitcnt(0x0F70);                                     // vmcnt(0)
+    }
     __syncthreads();
     if (nk > 0) load_frags(0, 0, 0);
 
@@ -128,9 +193,9 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_nt_dl_kernel(GemmArgs g) 
         load_frags(1, cur, 3);
         mfma_step(0);
         interleave_reads();
-        // tile kt+1 has landed (it is the only one in flight), this wave's reads of
+        // tile kt+1 has landed (it is the only one in flight) and this wave's reads of
         // the current stage are done: after the barrier the stage can be refilled
-        __builtin_amdgcn_s_waitcnt(0);                              // vmcnt(0) expcnt(0) lgkmcnt(0)
+        __builtin_amdgcn_s_waitcnt(0);                               // vmcnt(0) expcnt(0) lgkmcnt(0)
         __syncthreads();
         if (kt + 2 < nk) issue_tile(cur);
         if (kt + 1 < nk) load_frags(0, nxt, 0);
@@ -145,7 +210,7 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_nt_dl_kernel(GemmArgs g) 
     __syncthreads();
 
     // Epilogue through LDS, as in gemm_mfma_kernel.
-    void* C = g.epi.out_f32 ? (void*)((float*)g.C) : (void*)((bf16*)g.C);
+    void* C = g.C;
     constexpr int SW = WN + 4;
     lds_f32* strip = (lds_f32*)lds + wave * (32 * SW);
 #pragma unroll
@@ -173,17 +238,17 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_nt_dl_kernel(GemmArgs g) 
     }
 }
 
-// Conditions beyond mfma_shape_ok: plain NT problem, no batch, no causal band.
+// Conditions beyond mfma_shape_ok: a plain problem, no batch, no causal band.
 template <int BM, int BN>
-inline bool mfma_dl_shape_ok(const GemmArgs& g) {
-    return mfma_shape_ok<BM, BN>(g, false, false) && g.batch == 1 && g.causal == 0;
+inline bool mfma_dl_shape_ok(const GemmArgs& g, bool a_km, bool b_km) {
+    return mfma_shape_ok<BM, BN>(g, a_km, b_km) && g.batch == 1 && g.causal == 0;
 }
 
-template <int BM, int BN, int WGN>
-inline hipError_t launch_gemm_mfma_nt_dl(const GemmArgs& g, hipStream_t st) {
+template <int BM, int BN, bool A_KM, bool B_KM, int WGN>
+inline hipError_t launch_gemm_mfma_dl(const GemmArgs& g, hipStream_t st) {
     constexpr size_t lds = 2 * (size_t)(BM + BN) * MF_BK * 2;
     static_assert(lds <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
-    auto kern = gemm_mfma_nt_dl_kernel<BM, BN, WGN>;
+    auto kern = gemm_mfma_dl_kernel<BM, BN, A_KM, B_KM, WGN>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
