@@ -3,10 +3,10 @@
 // instructions, and the data of a tile is in flight for a whole k-tile of
 // matrix work. Same tiling, fragment double buffering, XCD-aware tile order and
 // epilogue as gemm_mfma_kernel; plain problems only (no batch, no causal band).
-// Measured on MI355X: 4-10 % faster than the register-staged kernel when both
-// operands are k-contiguous (NT) and more than one workgroup per compute unit
-// is resident; slower (up to 20 % at the 256x256 tile) when an operand is
-// m/n-contiguous, so the stage only uses it for NT products.
+// Measured on MI355X against the register-staged kernel: the four-wave 128x128
+// tile is 7-18 % faster in every layout once more than one workgroup per compute
+// unit is resident; the 256x256 tile gains 1-5 % for NT and TN and loses up to
+// 18 % for NN on wide-N shapes, so the stage keeps the staged kernel there.
 //
 // One such load moves 64 lanes x 16 bytes = 1 KB to consecutive LDS addresses
 // (lane l's 16 bytes land at base + 16 l), so a tile row cannot be padded.
@@ -24,7 +24,22 @@
 
 namespace amdp {
 
-typedef __attribute__((address_space(3))) void lds_void;
+// 16 bytes per lane from global memory to LDS: lane l's data lands at
+// lds_addr + 16 l (lds_addr uniform, it travels in M0). Written as an asm
+// statement on purpose: with the compiler's own builtin its wait-count pass
+// puts a full vmcnt(0) wait in front of every transposing LDS read that follows
+// (it cannot tell that those read the other LDS stage), which serialises the
+// loads with the matrix work. The waits that are needed are written out below:
+// vmcnt(0) before the barrier that publishes a stage.
+// M0 is saved and restored around the load, so the statement leaves no
+// register the compiler reserves changed.
+__device__ __forceinline__ void load16_to_lds(const void* g, lds_u8* lds_addr) {
+    unsigned saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0)
+                 : "s"((unsigned)(__UINTPTR_TYPE__)lds_addr), "v"(g)
+                 : "memory");
+}
 
 // One operand's tile: R rows (m or n) by 64 k. NW = waves in the workgroup.
 template <int R, bool KM, int NW>
@@ -118,11 +133,10 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_dl_kernel(GemmArgs g) {
     auto issue_tile = [&](int stage) {
 #pragma unroll
         for (int p = 0; p < TA::PW; ++p)
-            __builtin_amdgcn_global_load_lds(pa + p * a_pass, (lds_void*)(lds + stage + (wave + NW * p) * 1024), 16, 0, 0);
+            load16_to_lds(pa + p * a_pass, lds + stage + (wave + NW * p) * 1024);
 #pragma unroll
         for (int p = 0; p < TB::PW; ++p)
-            __builtin_amdgcn_global_load_lds(pb + p * b_pass,
-                                             (lds_void*)(lds + stage + TA::BYTES + (wave + NW * p) * 1024), 16, 0, 0);
+            load16_to_lds(pb + p * b_pass, lds + stage + TA::BYTES + (wave + NW * p) * 1024);
         pa += a_step;
         pb += b_step;
     };

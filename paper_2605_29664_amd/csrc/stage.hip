@@ -228,7 +228,8 @@ struct amdp_stage {
     int staged_slot = -1;   // activation slot whose gradient sits in the staging buffer
     bool use_tr = true;
     int force_tile = 0;
-    bool use_direct = true;        // NT products load tiles straight into LDS (AMDP_GEMM_DIRECT=0: through registers)
+    int use_direct = 1;           // plain products load tiles straight into LDS where measured faster
+                                  // (AMDP_GEMM_DIRECT=0: never, always through registers; 2: wherever the shape allows)
     Profiler prof;
     // Launch target of the helper functions: the caller's stream, or the side
     // stream while a gradient leaf (dW GEMM, bias / LayerNorm column sums) is
@@ -365,17 +366,18 @@ int gemm_bf16_layout(amdp_stage* st, const GemmArgs& g) {
         snprintf(name, sizeof(name), "gemm_generic_%s%s", A_KM ? "TN" : (B_KM ? "NN" : "NT"), g.batch > 1 ? "_batched" : "");
     ProfScope ps(st, name, gemm_flops(g), 0.0);
     hipError_t e;
-    // plain NT products (dX = dY W^T, logits) load their tiles straight into LDS: 4-10 % faster.
-    // (Measured for the other layouts too: m/n-contiguous operands lose up to 20 % that way.)
-    constexpr bool NT_LAYOUT = !A_KM && !B_KM;
-    const bool direct = NT_LAYOUT && st->use_direct && g.batch == 1 && g.causal == 0;
-    if (direct && pick == 0) {
-        e = launch_gemm_mfma_dl<256, 256, false, false, 4>(g, st->launch);
+    // Plain products (no batch, no causal band) load their tiles straight into LDS where
+    // that measured faster: the 128x128 tile in every layout once more than one workgroup
+    // per compute unit is resident (7-18 %; with fewer the eight-wave kernel below stays
+    // ahead), the 256x256 tile for NT and TN (1-5 %; NN measured up to 18 % slower there).
+    const bool direct = st->use_direct && g.batch == 1 && g.causal == 0, always = st->use_direct == 2;
+    constexpr bool NN_LAYOUT = !A_KM && B_KM;
+    if (direct && pick == 0 && (!NN_LAYOUT || always)) {
+        e = launch_gemm_mfma_dl<256, 256, A_KM, B_KM, 4>(g, st->launch);
         return hip_ok(e, name) ? AMDP_OK : AMDP_E_HIP;
     }
-    if (direct && pick == 1 && tiles(cand[1]) > st->n_cu) {
-        // (with at most one workgroup per compute unit the eight-wave kernel below stays ahead)
-        e = launch_gemm_mfma_dl<128, 128, false, false, 2>(g, st->launch);
+    if (direct && pick == 1 && (tiles(cand[1]) > st->n_cu || always)) {
+        e = launch_gemm_mfma_dl<128, 128, A_KM, B_KM, 2>(g, st->launch);
         return hip_ok(e, name) ? AMDP_OK : AMDP_E_HIP;
     }
     switch (pick) {
@@ -981,7 +983,7 @@ extern "C" int amdp_stage_create(const amdp_stage_config_t* cfg, void* workspace
     st->flash = flash_mode();
     if (const char* e = getenv("AMDP_GEMM_TR")) st->use_tr = atoi(e) != 0;
     if (const char* e = getenv("AMDP_GEMM_TILE")) st->force_tile = atoi(e);
-    if (const char* e = getenv("AMDP_GEMM_DIRECT")) st->use_direct = atoi(e) != 0;
+    if (const char* e = getenv("AMDP_GEMM_DIRECT")) st->use_direct = atoi(e);
     // parameter buffers, version slots and the padding behind them start at zero
     if (device_zero(st->launch, st->base, st->w.act) != AMDP_OK) {
         amdp_stage_destroy(st);

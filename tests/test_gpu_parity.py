@@ -77,12 +77,13 @@ def test_tile_bf16_head_dim_128(key):
     assert rep["ok"], worst_entries(rep)
 
 
-@pytest.mark.parametrize("direct", ["1", "0"])
+@pytest.mark.parametrize("direct", ["2", "1", "0"])
 @pytest.mark.parametrize("tile", ["256", "128", "128064", "64128", "64"])
 def test_tile_bf16_forced_tile(tile, direct):
     """Every matrix-core tile shape on the same workload (a tile that does not
     divide a product's shape leaves that product to the default choice), with
-    the NT products loading their tiles straight into LDS and through registers."""
+    the plain products loading their tiles straight into LDS wherever the shape
+    allows (2), where the dispatch rule says so (1), and never (0)."""
     os.environ["AMDP_GEMM_TILE"] = tile
     os.environ["AMDP_GEMM_DIRECT"] = direct
     rep = run_parity(W.TINY["gpt_tile"], n_windows=1, verbose=False)
