@@ -383,15 +383,19 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_kernel(GemmArgs g) {
     void* C = g.epi.out_f32 ? (void*)((float*)g.C + c_off) : (void*)((bf16*)g.C + c_off);
     constexpr int SW = WN + 4;                     // strip row stride in floats
     lds_f32* strip = (lds_f32*)lds + wave * (32 * SW);
+    // The strip is private to its wave and a wave's LDS operations complete in
+    // issue order, so after this barrier (every wave is done with the operand
+    // tiles) the passes below need no workgroup barrier between them.
+    __syncthreads();
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        __syncthreads();                           // previous strip fully read (first pass: main loop done)
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v)
                 strip[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * SW + j * 32 + (lane & 31)] = acc[i][j][v];
-        __syncthreads();
+        __builtin_amdgcn_wave_barrier();
         constexpr int CPR = WN / 8;                // 8-column chunks per strip row
         for (int it = 0; it < WN / 16; ++it) {
             const int c = lane + 64 * it;

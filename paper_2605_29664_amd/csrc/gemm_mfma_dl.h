@@ -229,13 +229,13 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_dl_kernel(GemmArgs g) {
     lds_f32* strip = (lds_f32*)lds + wave * (32 * SW);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        __syncthreads();
+        __builtin_amdgcn_wave_barrier();   // wave-private strip: no workgroup barrier needed (see gemm_mfma_kernel)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v)
                 strip[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * SW + j * 32 + (lane & 31)] = acc[i][j][v];
-        __syncthreads();
+        __builtin_amdgcn_wave_barrier();
         constexpr int CPR = WN / 8;
         for (int it = 0; it < WN / 16; ++it) {
             const int c = lane + 64 * it;
