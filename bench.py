@@ -197,8 +197,10 @@ def main():
             table[name] = row
         result["kernels"] = table
         result["roofline"] = dominant_gemm(prof)
-        result["roofline"]["note"] = ("as timed: kernels of the side stream run concurrently, so a launch shares "
-                                      "the compute units with others; see roofline_isolated")
+        result["side_stream"] = stage.amdp_stage_get_overlap()
+        result["roofline"]["note"] = (("as timed: kernels of the side stream run concurrently, so a launch shares "
+                                       "the compute units with others; see roofline_isolated") if result["side_stream"]
+                                      else "as timed: the side stream is off at this width, every kernel has the GPU to itself")
         def streaming(pr):
             out = {}
             for nm in ("grad_accumulate", "adam_update"):
@@ -214,10 +216,11 @@ def main():
         result["streaming"] = result["streaming_as_timed"]
         # (b) every kernel alone on the GPU (side stream off), same launches
         if len(steps) > cursor:
+            overlap_default = stage.amdp_stage_get_overlap()
             stage.amdp_stage_set_overlap(False)
             iso = profile_step(steps[cursor])
             cursor += 1
-            stage.amdp_stage_set_overlap(True)
+            stage.amdp_stage_set_overlap(overlap_default)
             result["roofline_isolated"] = dominant_gemm(iso)
             result["streaming"] = streaming(iso)
             gem = {n: r for n, r in iso.items() if n.startswith("gemm_") and r["ms"] > 0}

@@ -334,8 +334,12 @@ int amdp_apply_update(amdp_stage_t* stage, const amdp_adam_t* hp, uint32_t* new_
  * owns and joins it back into the caller's stream before returning, so the
  * caller still sees one stream; amdp_grad_accumulate uses the same side stream.
  * on = 0 keeps everything on the caller's stream (used to time kernels in
- * isolation); default is on. Results are bit-identical either way. */
+ * isolation). Default: on while (d_model / 256)^2 is below the number of compute
+ * units, off beyond (every product of the backward then fills the GPU on its
+ * own and concurrency measured no gain). Results are bit-identical either way. */
 int amdp_stage_set_overlap(amdp_stage_t* stage, int32_t on);
+/* *on (host) <- 1 when the side stream is in use, else 0. */
+int amdp_stage_get_overlap(const amdp_stage_t* stage, int32_t* on);
 
 /* The input embedding of the first stage and the output projection of the last
  * are one tied parameter held twice; before the update their gradient sums must

@@ -149,6 +149,7 @@ def lib():
         "amdp_grad_accumulate": (C.c_int, [vp, i32]),
         "amdp_apply_update": (C.c_int, [vp, P(amdp_adam_t), P(u32)]),
         "amdp_stage_set_overlap": (C.c_int, [vp, i32]),
+        "amdp_stage_get_overlap": (C.c_int, [vp, P(i32)]),
         "amdp_stage_join": (C.c_int, [vp]),
         "amdp_stage_set_fused_accumulate": (C.c_int, [vp, i32]),
         "amdp_tie_embedding_grads": (C.c_int, [vp, vp]),
@@ -169,7 +170,7 @@ EXPORTED = ["amdp_strerror", "amdp_last_hip_error", "amdp_schedule_generate", "a
             "amdp_stage_create", "amdp_stage_destroy", "amdp_stage_set_state", "amdp_stage_get_state",
             "amdp_stage_get_staged_grad", "amdp_stage_resident_versions", "amdp_stage_forward",
             "amdp_stage_backward", "amdp_grad_accumulate", "amdp_apply_update",
-            "amdp_stage_set_overlap", "amdp_stage_join", "amdp_stage_set_fused_accumulate", "amdp_tie_embedding_grads",
+            "amdp_stage_set_overlap", "amdp_stage_get_overlap", "amdp_stage_join", "amdp_stage_set_fused_accumulate", "amdp_tie_embedding_grads",
             "amdp_stage_profile_begin", "amdp_stage_profile_end"]
 
 
@@ -392,6 +393,11 @@ class Stage:
 
     def amdp_stage_set_overlap(self, on):
         _check(lib().amdp_stage_set_overlap(self.handle, int(bool(on))), "amdp_stage_set_overlap")
+
+    def amdp_stage_get_overlap(self):
+        on = C.c_int32(0)
+        _check(lib().amdp_stage_get_overlap(self.handle, C.byref(on)), "amdp_stage_get_overlap")
+        return bool(on.value)
 
     def amdp_stage_profile_begin(self):
         _check(lib().amdp_stage_profile_begin(self.handle), "amdp_stage_profile_begin")

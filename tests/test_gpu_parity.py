@@ -195,7 +195,9 @@ def test_side_stream_on_off_bit_identical():
     for overlap in (True, False):
         gpu = GpuStage(w, act_slots=12, stash_slots=3)
         gpu.set_state(theta0)
+        assert gpu.stage.amdp_stage_get_overlap()          # narrow stage: the side stream is on by default
         gpu.stage.amdp_stage_set_overlap(overlap)
+        assert gpu.stage.amdp_stage_get_overlap() == overlap
         y = torch.empty((w.tokens, w.d_model), dtype=torch.bfloat16, device="cuda:0")
         dx = torch.empty_like(y)
         for e in ev:
