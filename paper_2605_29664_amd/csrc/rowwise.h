@@ -183,22 +183,34 @@ __global__ __launch_bounds__(256) void colreduce_partial_kernel(const T* __restr
         }
     }
 }
-// Stage 2: out[c] = sum over chunks. A block owns 64 columns; its 4 groups of
-// 64 threads each sum every 4th chunk, then the groups are added in fixed order.
-// accumulate != 0: out[c] += that sum.
+// Stage 2: out[c] = sum over chunks. A block owns 16 columns; its 16 groups of
+// 16 threads each sum every 16th chunk (four loads in flight per thread: the
+// sums are short, so the kernel lives on memory latency), then the groups are
+// added in fixed order. accumulate != 0: out[c] += that sum.
 __global__ __launch_bounds__(256) void colreduce_final_kernel(const float* __restrict__ partial,
                                                              float* __restrict__ out, int width, int chunks,
                                                              int accumulate) {
-    __shared__ float red[4][64];
-    const int j = threadIdx.x & 63, grp = threadIdx.x >> 6;
-    const int c = blockIdx.x * 64 + j;
-    float s = 0.f;
-    if (c < width)
-        for (int k = grp; k < chunks; k += 4) s += partial[(long)k * width + c];
-    red[grp][j] = s;
+    __shared__ float red[16][17];
+    const int j = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int c = blockIdx.x * 16 + j;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (c < width) {
+        const float* p = partial + c;
+        int k = grp;
+        for (; k + 48 < chunks; k += 64) {
+            s0 += p[(long)k * width];
+            s1 += p[(long)(k + 16) * width];
+            s2 += p[(long)(k + 32) * width];
+            s3 += p[(long)(k + 48) * width];
+        }
+        for (; k < chunks; k += 16) s0 += p[(long)k * width];
+    }
+    red[grp][j] = (s0 + s1) + (s2 + s3);
     __syncthreads();
     if (grp == 0 && c < width) {
-        const float t = (red[0][j] + red[1][j]) + (red[2][j] + red[3][j]);
+        float t = 0.f;
+#pragma unroll
+        for (int g = 0; g < 16; ++g) t += red[g][j];
         out[c] = accumulate ? out[c] + t : t;
     }
 }

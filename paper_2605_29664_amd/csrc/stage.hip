@@ -188,7 +188,7 @@ void carve(const Dims& d, const amdp_stage_config_t& c, Carve* w) {
         const size_t NDp = pk ? (size_t)d.N * d.H * flash_head_dim(d) * d.esz : 0;
         w->pk_qkv = take(3 * NDp); w->pk_dqkv = take(3 * NDp); w->pk_o = take(NDp); w->pk_do = take(NDp);
     }
-    w->partial_chunks = 64;
+    w->partial_chunks = 256;
     const size_t maxw = (size_t)std::max(std::max(3 * d.D, d.F), 2 * d.D);
     w->partial = take((size_t)w->partial_chunks * maxw * 4);
     w->row_loss = take((size_t)d.N * 4);
@@ -446,7 +446,7 @@ int colreduce(amdp_stage* st, const void* dy, const void* x, const float* stats,
     // enough row chunks to put ~4 blocks on every compute unit, at least 8 rows each
     constexpr int V = Vec<T>::N;
     const int col_blocks = (C + 64 * V - 1) / (64 * V);
-    int chunks = std::min(st->w.partial_chunks, std::max(1, 512 / col_blocks));
+    int chunks = std::min(st->w.partial_chunks, std::max(1, 4 * st->n_cu / col_blocks));
     int rpc = std::max(8, (d.N + chunks - 1) / chunks);
     chunks = (d.N + rpc - 1) / rpc;
     float* partial = st->at<float>(st->w.partial);
@@ -455,7 +455,7 @@ int colreduce(amdp_stage* st, const void* dy, const void* x, const float* stats,
                        st->launch, (const T*)dy, (const T*)x, stats, partial, d.N, C, rpc);
     TRY(after_launch());
     const int width = LN ? 2 * C : C;
-    hipLaunchKernelGGL(colreduce_final_kernel, dim3((width + 63) / 64), dim3(256), 0, st->launch, partial,
+    hipLaunchKernelGGL(colreduce_final_kernel, dim3((width + 15) / 16), dim3(256), 0, st->launch, partial,
                        out, width, chunks, st->fused_acc ? 1 : 0);
     return after_launch();
 }
