@@ -54,7 +54,11 @@ struct DlTile {
     // Byte offset from the tile's first element (row 0, k 0) of what this lane
     // fetches in pass 0; rs = elements between consecutive m/n rows, ks =
     // elements between consecutive k.
-    __device__ static __forceinline__ long lane_goff(int wave, int lane, long rs, long ks) {
+    // `valid` = rows of the tile that exist (a multiple of 64; R except in a
+    // ragged last tile). Rows beyond it are never stored, so their LDS content
+    // may be anything: a lane that would fetch them fetches an existing row
+    // instead (same address arithmetic, no access outside the matrix).
+    __device__ static __forceinline__ long lane_goff(int wave, int lane, long rs, long ks, int valid = R) {
         if constexpr (!KM) {
             const int row = 8 * wave + (lane >> 3), pos = lane & 7;
             const int f = (row >> 1) & 7;
@@ -62,9 +66,16 @@ struct DlTile {
         } else {
             const int o = 16 * lane;                          // LDS byte inside the 1 KB chunk
             const int krow = CHUNK_ROWS * wave + o / ROWB, pb = o % ROWB;
-            const int b = (((pb >> 6) ^ (krow & 3)) << 6) | (pb & 63);
+            int b = (((pb >> 6) ^ (krow & 3)) << 6) | (pb & 63);
+            if (b >= valid * 2) b &= 127;                     // the first 64 rows always exist
             return (long)krow * ks * 2 + b;
         }
+    }
+    // Pass whose global rows pass p fetches: itself, or (k-contiguous operand, rows of
+    // the pass beyond `valid`) the pass that covers the same rows modulo 64.
+    __device__ static __forceinline__ int source_pass(int p, int valid) {
+        if constexpr (KM) return p;
+        else return p * 8 * NW < valid ? p : p % (64 / (8 * NW));
     }
     // pass p adds p * pass_gstride (the swizzle terms do not change with the pass)
     __device__ static __forceinline__ long pass_gstride(long rs, long ks) {
@@ -100,7 +111,10 @@ struct DlTile {
     }
 };
 
-template <int BM, int BN, bool A_KM, bool B_KM, int WGN>
+// EDGE: M and N need only be multiples of 64; the last tile of a row or column
+// of tiles is then ragged, loads of its missing rows are redirected (see
+// DlTile::lane_goff) and the epilogue skips them.
+template <int BM, int BN, bool A_KM, bool B_KM, int WGN, bool EDGE = false>
 __global__ __launch_bounds__(128 * WGN) void gemm_mfma_dl_kernel(GemmArgs g) {
     constexpr int NT = 128 * WGN, NW = NT / 64;
     constexpr int WM = BM / 2, WN = BN / WGN;
@@ -115,7 +129,7 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_dl_kernel(GemmArgs g) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
 
-    const int tiles_m = g.M / BM, tiles_n = g.N / BN, ntiles = tiles_m * tiles_n;
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN, ntiles = tiles_m * tiles_n;
     int pid = blockIdx.x;
     if (ntiles % 8 == 0) pid = (pid % 8) * (ntiles / 8) + pid / 8;
     constexpr int GROUP = 8;
@@ -126,17 +140,18 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_dl_kernel(GemmArgs g) {
     const int pn = (pid % per_group) / gsize;
     const int m0 = pm * BM, n0 = pn * BN;
 
-    const char* pa = (const char*)((const bf16*)g.A + (long)m0 * g.a_rs) + TA::lane_goff(wave, lane, g.a_rs, g.a_cs);
-    const char* pb = (const char*)((const bf16*)g.B + (long)n0 * g.b_cs) + TB::lane_goff(wave, lane, g.b_cs, g.b_rs);
+    const int valid_m = EDGE ? min(BM, g.M - m0) : BM, valid_n = EDGE ? min(BN, g.N - n0) : BN;
+    const char* pa = (const char*)((const bf16*)g.A + (long)m0 * g.a_rs) + TA::lane_goff(wave, lane, g.a_rs, g.a_cs, valid_m);
+    const char* pb = (const char*)((const bf16*)g.B + (long)n0 * g.b_cs) + TB::lane_goff(wave, lane, g.b_cs, g.b_rs, valid_n);
     const long a_pass = TA::pass_gstride(g.a_rs, g.a_cs), b_pass = TB::pass_gstride(g.b_cs, g.b_rs);
     const long a_step = TA::ktile_gstride(g.a_cs), b_step = TB::ktile_gstride(g.b_rs);
     auto issue_tile = [&](int stage) {
 #pragma unroll
         for (int p = 0; p < TA::PW; ++p)
-            load16_to_lds(pa + p * a_pass, lds + stage + (wave + NW * p) * 1024);
+            load16_to_lds(pa + (EDGE ? TA::source_pass(p, valid_m) : p) * a_pass, lds + stage + (wave + NW * p) * 1024);
 #pragma unroll
         for (int p = 0; p < TB::PW; ++p)
-            load16_to_lds(pb + p * b_pass, lds + stage + TA::BYTES + (wave + NW * p) * 1024);
+            load16_to_lds(pb + (EDGE ? TB::source_pass(p, valid_n) : p) * b_pass, lds + stage + TA::BYTES + (wave + NW * p) * 1024);
         pa += a_step;
         pb += b_step;
     };
@@ -247,7 +262,7 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_dl_kernel(GemmArgs g) {
             for (int k = 0; k < 4; ++k) { v8[k] = lo[k]; v8[4 + k] = hi[k]; }
             const long m = m0 + wm * WM + i * 32 + row;
             const long n = n0 + wn * WN + cc * 8;
-            epilogue_store8(g.epi, C, g.ldc, m, n, v8);
+            if (!EDGE || (m < g.M && n < g.N)) epilogue_store8(g.epi, C, g.ldc, m, n, v8);
         }
     }
 }
@@ -258,18 +273,24 @@ inline bool mfma_dl_shape_ok(const GemmArgs& g, bool a_km, bool b_km) {
     return mfma_shape_ok<BM, BN>(g, a_km, b_km) && g.batch == 1 && g.causal == 0;
 }
 
-template <int BM, int BN, bool A_KM, bool B_KM, int WGN>
+// The EDGE instantiation's conditions: as mfma_dl_shape_ok, with M and N multiples
+// of 64 instead of the tile.
+inline bool mfma_dl_edge_shape_ok(const GemmArgs& g, bool a_km, bool b_km) {
+    return mfma_shape_ok<64, 64>(g, a_km, b_km) && g.batch == 1 && g.causal == 0;
+}
+
+template <int BM, int BN, bool A_KM, bool B_KM, int WGN, bool EDGE = false>
 inline hipError_t launch_gemm_mfma_dl(const GemmArgs& g, hipStream_t st) {
     constexpr size_t lds = 2 * (size_t)(BM + BN) * MF_BK * 2;
     static_assert(lds <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
-    auto kern = gemm_mfma_dl_kernel<BM, BN, A_KM, B_KM, WGN>;
+    auto kern = gemm_mfma_dl_kernel<BM, BN, A_KM, B_KM, WGN, EDGE>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3((g.M / BM) * (g.N / BN)), dim3(128 * WGN), lds, st, g);
+    hipLaunchKernelGGL(kern, dim3(((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN)), dim3(128 * WGN), lds, st, g);
     return hipGetLastError();
 }
 

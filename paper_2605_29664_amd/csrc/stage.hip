@@ -337,19 +337,31 @@ hipError_t launch_tile(amdp_stage* st, const GemmArgs& g) {
 }
 
 // Tile choice, from measurement on MI355X: the largest tile that still fills
-// the GPU wins (the 256x256 tile needs a workgroup for every compute unit, the
-// smaller ones three quarters of them); when no tile gets there, the one with
-// the most workgroups does.
+// the GPU wins (the 256x256 tile needs a workgroup for every compute unit and
+// at least 70 % of its last round of workgroups, the smaller ones three
+// quarters of the units); when no tile gets there, the one with the most
+// workgroups does. Plain products (no batch, no causal band) whose M or N is a
+// multiple of 64 but not of the tile run the 128x128 and 256x256 tiles with a
+// ragged last tile on the direct-to-LDS kernel.
 template <bool A_KM, bool B_KM>
 int gemm_bf16_layout(amdp_stage* st, const GemmArgs& g) {
-    struct Cand { int bm, bn; bool ok; };
-    const Cand cand[5] = {{256, 256, mfma_shape_ok<256, 256>(g, A_KM, B_KM)}, {128, 128, mfma_shape_ok<128, 128>(g, A_KM, B_KM)},
-                          {128, 64, mfma_shape_ok<128, 64>(g, A_KM, B_KM)},   {64, 128, mfma_shape_ok<64, 128>(g, A_KM, B_KM)},
-                          {64, 64, mfma_shape_ok<64, 64>(g, A_KM, B_KM)}};
-    auto tiles = [&](const Cand& c) { return (long)(g.M / c.bm) * (g.N / c.bn) * g.batch; };
+    const bool direct = st->use_direct && g.batch == 1 && g.causal == 0, always = st->use_direct == 2;
+    const bool ragged_ok = direct && mfma_dl_edge_shape_ok(g, A_KM, B_KM);
+    struct Cand { int bm, bn; bool exact, ok; };
+    Cand cand[5] = {{256, 256, mfma_shape_ok<256, 256>(g, A_KM, B_KM), false}, {128, 128, mfma_shape_ok<128, 128>(g, A_KM, B_KM), false},
+                    {128, 64, mfma_shape_ok<128, 64>(g, A_KM, B_KM), false},   {64, 128, mfma_shape_ok<64, 128>(g, A_KM, B_KM), false},
+                    {64, 64, mfma_shape_ok<64, 64>(g, A_KM, B_KM), false}};
+    for (int i = 0; i < 5; ++i) cand[i].ok = cand[i].exact || (i < 2 && ragged_ok);
+    auto tiles = [&](const Cand& c) { return (long)((g.M + c.bm - 1) / c.bm) * ((g.N + c.bn - 1) / c.bn) * g.batch; };
+    auto fills = [&](int i) {
+        const long t = tiles(cand[i]);
+        if (i > 0) return t >= st->n_cu * 3 / 4;
+        const long rounds = (t + st->n_cu - 1) / st->n_cu;
+        return t >= st->n_cu && 10 * t >= 7 * rounds * st->n_cu;
+    };
     int pick = -1;
     for (int i = 0; i < 5 && pick < 0; ++i)
-        if (cand[i].ok && tiles(cand[i]) >= (i == 0 ? st->n_cu : st->n_cu * 3 / 4)) pick = i;
+        if (cand[i].ok && fills(i)) pick = i;
     if (pick < 0)
         for (int i = 0; i < 5; ++i)
             if (cand[i].ok && (pick < 0 || tiles(cand[i]) > tiles(cand[pick]))) pick = i;
@@ -366,11 +378,15 @@ int gemm_bf16_layout(amdp_stage* st, const GemmArgs& g) {
         snprintf(name, sizeof(name), "gemm_generic_%s%s", A_KM ? "TN" : (B_KM ? "NN" : "NT"), g.batch > 1 ? "_batched" : "");
     ProfScope ps(st, name, gemm_flops(g), 0.0);
     hipError_t e;
-    // Plain products (no batch, no causal band) load their tiles straight into LDS where
-    // that measured faster: the 128x128 tile in every layout once more than one workgroup
-    // per compute unit is resident (7-18 %; with fewer the eight-wave kernel below stays
-    // ahead), the 256x256 tile for NT and TN (1-5 %; NN measured up to 18 % slower there).
-    const bool direct = st->use_direct && g.batch == 1 && g.causal == 0, always = st->use_direct == 2;
+    if (pick >= 0 && pick < 2 && !cand[pick].exact) {
+        e = pick == 0 ? launch_gemm_mfma_dl<256, 256, A_KM, B_KM, 4, true>(g, st->launch)
+                      : launch_gemm_mfma_dl<128, 128, A_KM, B_KM, 2, true>(g, st->launch);
+        return hip_ok(e, name) ? AMDP_OK : AMDP_E_HIP;
+    }
+    // Plain products load their tiles straight into LDS where that measured faster: the
+    // 128x128 tile in every layout once more than one workgroup per compute unit is
+    // resident (7-18 %; with fewer the eight-wave kernel below stays ahead), the
+    // 256x256 tile for NT and TN (1-5 %; NN measured up to 18 % slower there).
     constexpr bool NN_LAYOUT = !A_KM && B_KM;
     if (direct && pick == 0 && (!NN_LAYOUT || always)) {
         e = launch_gemm_mfma_dl<256, 256, A_KM, B_KM, 4>(g, st->launch);

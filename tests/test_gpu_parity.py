@@ -91,6 +91,19 @@ def test_tile_bf16_forced_tile(tile, direct):
     assert rep["ok"], worst_entries(rep)
 
 
+@pytest.mark.parametrize("key", ["gpt_tile_edge", "gpt_tile64"])
+@pytest.mark.parametrize("tile", ["256", "128"])
+def test_tile_bf16_ragged_last_tile(key, tile):
+    """Widths and token counts that are multiples of 64 but not of the tile: the
+    last tile of a row or column of tiles has 64, 128 or 192 of its 256 rows
+    (64 of 128), its missing rows are neither loaded from outside the matrix
+    nor stored."""
+    os.environ["AMDP_GEMM_TILE"] = tile
+    rep = run_parity(W.TINY[key], n_windows=1, verbose=False)
+    _report(f"{key}_ragged_{tile}", rep)
+    assert rep["ok"], worst_entries(rep)
+
+
 @pytest.mark.parametrize("key", ["gpt_tile64", "bert_dh50", "bert_tile_dh50", "gpt_tile_dh96"])
 def test_bf16_multiples_of_64_and_odd_head_dims(key):
     rep = run_parity(W.TINY[key], n_windows=1, verbose=False)

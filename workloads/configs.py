@@ -117,6 +117,10 @@ TINY = {
     # multiples of 64 but not of 128: the 64-row matrix tiles
     "gpt_tile64": StageWorkload("tile64_gpt", 22, GPT_PRELN_CAUSAL, 2, 192, 3, 768, 128, 2, BF16,
                                 depth=4, pipelines=2, stage=1, threshold=4),
+    # every ragged last tile the 128- and 256-wide GEMM tiles can meet: widths 320 = 256 + 64,
+    # 640 = 2*256 + 128, 960 = 3*256 + 192; 384 tokens = 256 + 128
+    "gpt_tile_edge": StageWorkload("tile_edge_gpt", 29, GPT_PRELN_CAUSAL, 2, 320, 5, 640, 128, 3, BF16,
+                                   depth=4, pipelines=2, stage=1, threshold=4),
     # head dimension 50 (the paper's BERT-style width / heads): no fused attention, unaligned heads
     "bert_dh50": StageWorkload("tiny_bert_dh50", 23, BERT_POSTLN_BIDIR, 1, 400, 8, 800, 24, 2, BF16,
                                depth=4, pipelines=2, stage=1, threshold=4),
