@@ -331,8 +331,16 @@ int amdp_apply_update(amdp_stage_t* stage, const amdp_adam_t* hp, uint32_t* new_
 
 /* Backward enqueues the parameter-gradient work (dW GEMMs, bias and LayerNorm
  * column sums), which is off the dX critical path, on a side stream the stage
- * owns and joins it back into the caller's stream before returning, so the
- * caller still sees one stream; amdp_grad_accumulate uses the same side stream.
+ * owns; amdp_grad_accumulate uses the same side stream. The caller still sees
+ * one stream: dX is complete in stream order when backward returns, dY (and a
+ * dX the input layer's gradient reads) may be overwritten in stream order at
+ * once, and every call that reads or changes what the side stream writes
+ * (amdp_stage_get_staged_grad, amdp_stage_get_state, amdp_stage_set_state,
+ * amdp_apply_update, amdp_tie_embedding_grads, amdp_stage_join) first makes the
+ * caller's stream wait for it. What keeps running beside the caller's next
+ * calls reads only the stage's workspace: the next backward waits for it
+ * before reusing the scratch it reads, and so does the forward that reuses
+ * its activation slot.
  * on = 0 keeps everything on the caller's stream (used to time kernels in
  * isolation). Default: on while (d_model / 256)^2 is below the number of compute
  * units, off beyond (every product of the backward then fills the GPU on its
@@ -363,11 +371,11 @@ int amdp_tie_embedding_grads(amdp_stage_t* first, amdp_stage_t* last);
  * accumulate. */
 int amdp_stage_set_fused_accumulate(amdp_stage_t* stage, int32_t on);
 
-/* Orders everything the stage has enqueued on its own side stream (at most the
- * accumulations since the last join) before whatever the caller enqueues next
+/* Orders everything the stage has enqueued on its own side stream (gradient
+ * leaves of the last backward, accumulations) before whatever the caller enqueues next
  * on its stream. Needed only by a caller that wants a point where the stage's
  * stream alone carries all of its work: before ending a HIP-graph capture that
- * contains amdp_grad_accumulate, or before reusing the workspace for something
+ * contains amdp_stage_backward or amdp_grad_accumulate, or before reusing the workspace for something
  * else. Enqueues an event wait; does not block the host. */
 int amdp_stage_join(amdp_stage_t* stage);
 

@@ -240,6 +240,18 @@ struct amdp_stage {
     int n_cu = 256;                // compute units of the device
     hipEvent_t events[16] = {};
     int ev_next = 0;
+    // A backward leaves its gradient leaves running on the side stream. What must wait
+    // for them: the next backward (it reuses the per-layer scratch they read) and the
+    // forward that reuses the activation slot they read; both wait for the event
+    // recorded behind the leaves, nothing else does. free_seq orders free slots so
+    // that a forward takes the one whose leaves are oldest.
+    bool lazy_join = true;           // AMDP_LAZY_JOIN=0: backward ends with a full join (measurement)
+    hipEvent_t input_ev = nullptr;   // behind the leaves that read the caller's dY
+    hipEvent_t leaves_ev[MAX_ASLOTS] = {};
+    bool leaves_pending[MAX_ASLOTS] = {};
+    int last_leaves = -1;
+    uint64_t free_seq[MAX_ASLOTS] = {};
+    uint64_t free_counter = 0;
     bool overlap = true;
     bool fused_acc = false;        // backward adds parameter gradients into G directly
     int flash = 1;          // fused attention: 1 on (default), 0 off, 2 test mode: run after the three-kernel path
@@ -792,6 +804,25 @@ int join_leaves(amdp_stage* st) {
     hipEvent_t ev = st->next_event();
     HIP_TRY(hipEventRecord(ev, st->side));
     HIP_TRY(hipStreamWaitEvent(st->stream, ev, 0));
+    for (int i = 0; i < st->cfg.act_slots; ++i) st->leaves_pending[i] = false;
+    st->last_leaves = -1;
+    return AMDP_OK;
+}
+// End of a backward: remember where its leaves end instead of waiting for them.
+int mark_leaves(amdp_stage* st, int aslot) {
+    if (!st->overlap) return AMDP_OK;
+    if (!st->lazy_join) return join_leaves(st);
+    HIP_TRY(hipEventRecord(st->leaves_ev[aslot], st->side));
+    st->leaves_pending[aslot] = true;
+    st->last_leaves = aslot;
+    return AMDP_OK;
+}
+// The main stream waits for the leaves of the backward that used `aslot`, if they may still run.
+int wait_leaves_of(amdp_stage* st, int aslot) {
+    if (aslot < 0 || !st->leaves_pending[aslot]) return AMDP_OK;
+    HIP_TRY(hipStreamWaitEvent(st->stream, st->leaves_ev[aslot], 0));
+    st->leaves_pending[aslot] = false;
+    if (st->last_leaves == aslot) st->last_leaves = -1;
     return AMDP_OK;
 }
 #define LEAF(stmts) do { Leaf leaf_(st); if (!leaf_.ok) return AMDP_E_HIP; stmts } while (0)
@@ -807,6 +838,7 @@ int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, co
     void* dP = st->at<>(st->w.dP);      // main chain only
 
     const void* dcur = dY;
+    bool dy_leaves = false;
     if (d.lm) {
         const SlotLayout& sl = st->w.slot;
         void* dz = st->at<>(st->w.lm_dz);
@@ -883,8 +915,18 @@ int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, co
                    TRY(linear_dw(st, S + a.xin, dqkv, G(W_QKV), d.N, 3 * d.D, d.D)); });
             TRY(linear_dx(st, dqkv, P(W_QKV), nullptr, tc, dnext, d.N, 3 * d.D, d.D));
         }
+        // the leaves of this layer read the caller's dY: remember where they end
+        if (dcur == dY && dY && st->overlap) {
+            HIP_TRY(hipEventRecord(st->input_ev, st->side));
+            dy_leaves = true;
+        }
         dcur = dnext;
     }
+    // The caller may reuse its buffers as soon as its stream gets past this call: the
+    // main stream waits for the few leaves that read dY (they were enqueued first and
+    // are long done), and for all of them when the input layer's leaves read the
+    // caller's dX; every other leaf reads the stage's own memory and keeps running.
+    if (dy_leaves) HIP_TRY(hipStreamWaitEvent(st->stream, st->input_ev, 0));
     if (d.emb) {
         // gradient of the input layer from dcur = d loss / d (block input)
         const int32_t* tokens = (const int32_t*)(S + st->w.slot.tokens);
@@ -901,8 +943,9 @@ int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, co
                                (const T*)dcur, tokens, g + d.off_tok(), d.N, d.D, d.V, acc);
             TRY(after_launch());
         });
+        if (dcur == dX && dX) return join_leaves(st);
     }
-    return join_leaves(st);
+    return mark_leaves(st, aslot);
 }
 
 template <class T>
@@ -993,6 +1036,9 @@ extern "C" int amdp_stage_create(const amdp_stage_config_t* cfg, void* workspace
         bool ok = hip_ok(hipStreamCreateWithFlags(&st->side, hipStreamNonBlocking), "hipStreamCreateWithFlags");
         for (int i = 0; ok && i < 16; ++i)
             ok = hip_ok(hipEventCreateWithFlags(&st->events[i], hipEventDisableTiming), "hipEventCreateWithFlags");
+        for (int i = 0; ok && i < cfg->act_slots; ++i)
+            ok = hip_ok(hipEventCreateWithFlags(&st->leaves_ev[i], hipEventDisableTiming), "hipEventCreateWithFlags");
+        ok = ok && hip_ok(hipEventCreateWithFlags(&st->input_ev, hipEventDisableTiming), "hipEventCreateWithFlags");
         if (!ok) { amdp_stage_destroy(st); return AMDP_E_HIP; }
     }
     // The side stream pays while the backward's products leave compute units idle. Once
@@ -1002,6 +1048,7 @@ extern "C" int amdp_stage_create(const amdp_stage_config_t* cfg, void* workspace
     st->overlap = (long)(st->d.D / 256) * (st->d.D / 256) < st->n_cu;
     if (ov) st->overlap = atoi(ov) != 0;
     st->flash = flash_mode();
+    if (const char* e = getenv("AMDP_LAZY_JOIN")) st->lazy_join = atoi(e) != 0;
     if (const char* e = getenv("AMDP_GEMM_TR")) st->use_tr = atoi(e) != 0;
     if (const char* e = getenv("AMDP_GEMM_TILE")) st->force_tile = atoi(e);
     if (const char* e = getenv("AMDP_GEMM_DIRECT")) st->use_direct = atoi(e);
@@ -1021,6 +1068,8 @@ extern "C" int amdp_stage_destroy(amdp_stage_t* st) {
         hipStreamDestroy(st->side);
     }
     for (hipEvent_t e : st->events) if (e) hipEventDestroy(e);
+    for (hipEvent_t e : st->leaves_ev) if (e) hipEventDestroy(e);
+    if (st->input_ev) hipEventDestroy(st->input_ev);
     delete st;
     return AMDP_OK;
 }
@@ -1095,9 +1144,11 @@ extern "C" int amdp_stage_forward(amdp_stage_t* st, int32_t mb, uint32_t version
     if (st->find_mb(mb) >= 0) return AMDP_E_MB_STATE;
     const int vslot = st->find_version(version);
     if (vslot < 0) return AMDP_E_VERSION;
-    int aslot = -1;
-    for (int i = 0; i < st->cfg.act_slots; ++i) if (!st->as[i].used) { aslot = i; break; }
+    int aslot = -1;                     // the free slot that has been free longest
+    for (int i = 0; i < st->cfg.act_slots; ++i)
+        if (!st->as[i].used && (aslot < 0 || st->free_seq[i] < st->free_seq[aslot])) aslot = i;
     if (aslot < 0) return AMDP_E_NO_SLOT;
+    TRY(wait_leaves_of(st, aslot));     // gradient leaves of its previous minibatch may still read it
     int rc = d.bf ? forward_impl<bf16>(st, aslot, vslot, X, aux, out)
                   : forward_impl<float>(st, aslot, vslot, X, aux, out);
     if (rc != AMDP_OK) return rc;
@@ -1119,6 +1170,7 @@ extern "C" int amdp_stage_backward(amdp_stage_t* st, int32_t mb, uint32_t versio
     // the padding mask was saved with the activations (the fused attention
     // backward recomputes the probabilities and needs it again)
     const int32_t* valid = (!d.causal && !d.lm) ? (const int32_t*)(st->act_ptr(aslot) + st->w.slot.valid) : nullptr;
+    TRY(wait_leaves_of(st, st->last_leaves));   // the previous backward's leaves read the scratch this one rewrites
     int rc = d.bf ? backward_impl<bf16>(st, aslot, vslot, valid, dY, dX)
                   : backward_impl<float>(st, aslot, vslot, valid, dY, dX);
     if (rc != AMDP_OK) return rc;
@@ -1149,6 +1201,7 @@ extern "C" int amdp_grad_accumulate(amdp_stage_t* st, int32_t mb) {
         TRY(after_launch());
     }
     st->as[aslot] = ASlot();
+    st->free_seq[aslot] = ++st->free_counter;
     st->staged_slot = -1;
     return AMDP_OK;
 }

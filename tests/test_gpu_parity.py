@@ -231,6 +231,34 @@ def test_side_stream_on_off_bit_identical():
         assert np.array_equal(a, b)
 
 
+def test_caller_may_overwrite_dy_right_after_backward():
+    """Gradient leaves keep running on the side stream after backward returns,
+    and the first ones read the caller's dY: overwriting dY on the caller's
+    stream right behind the call must not change the gradient."""
+    import torch
+    from oracle.stage import Stage as OStage
+    w = W.TINY["gpt_tile"]
+    theta0 = W.make_theta(w, OStage.from_workload(w).layout)
+    x = torch.from_numpy(W.make_x(w, 0)).to("cuda:0").to(torch.bfloat16)
+    dy0 = torch.from_numpy(W.make_dy(w, 0)).to("cuda:0").to(torch.bfloat16)
+    grads = []
+    for clobber in (False, True):
+        gpu = GpuStage(w)
+        gpu.set_state(theta0)
+        assert gpu.stage.amdp_stage_get_overlap()
+        y, dx, dy = torch.empty_like(x), torch.empty_like(x), dy0.clone()
+        gpu.stage.amdp_stage_forward(0, 0, x, None, y)
+        gpu.stage.amdp_stage_backward(0, 0, dy, dx)
+        if clobber:
+            dy.fill_(float("nan"))
+        g = torch.empty(gpu.n, dtype=torch.float32, device="cuda:0")
+        gpu.stage.amdp_stage_get_staged_grad(g)
+        torch.cuda.synchronize()
+        grads.append(g.cpu().numpy())
+        gpu.stage.close()
+    assert np.all(np.isfinite(grads[1])) and np.array_equal(grads[0], grads[1])
+
+
 @pytest.mark.parametrize("key", ["gpt_tile", "lmhead_tile", "bert_mid", "gpt"])
 def test_fused_accumulate_bit_identical(key):
     """amdp_stage_set_fused_accumulate(1): backward adds into G directly. A
