@@ -89,6 +89,7 @@ def test_streaming_kernels_largest_config():
     print("\n[cfg5 streaming kernels] start", flush=True)
     gpu = GpuStage(w, act_slots=2, stash_slots=1)
     n = gpu.n
+    assert not gpu.stage.amdp_stage_get_overlap(), "d_model 4096: the side stream is off by default"
     import paper_2605_29664_amd as amdp
     layout = amdp.amdp_stage_param_layout(gpu.cfg)
     gen = torch.Generator(device="cuda").manual_seed(296645)
