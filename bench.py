@@ -215,6 +215,7 @@ def main():
         result["streaming_as_timed"] = streaming(prof)
         result["streaming"] = result["streaming_as_timed"]
         # (b) every kernel alone on the GPU (side stream off), same launches
+        iso = None
         if len(steps) > cursor:
             overlap_default = stage.amdp_stage_get_overlap()
             stage.amdp_stage_set_overlap(False)
@@ -232,6 +233,45 @@ def main():
                                               **({"tflops": round(r["flops"] / r["ms"] / 1e9, 2)} if r["flops"] > 0 else {}),
                                               **({"gbs": round(r["bytes"] / r["ms"] / 1e6, 1)} if r["bytes"] > 0 else {})}
                                           for n, r in sorted(iso.items(), key=lambda kv: -kv[1]["ms"]) if r["ms"] > 0}
+
+        # kernel-level matrix-core figure: every GEMM and fused-attention launch of the step
+        # (algorithmic flops / summed durations, each kernel alone on the GPU when that pass ran)
+        src = iso if iso is not None else prof
+        mat = {n: r for n, r in src.items() if (n.startswith("gemm_") or n.startswith("flash_attention")) and r["ms"] > 0}
+        if mat:
+            tf, tm = sum(x["flops"] for x in mat.values()), sum(x["ms"] for x in mat.values())
+            result["matrix_kernels"] = {"tflops": tf / tm / 1e9, "frac_of_peak": tf / tm / 1e9 / peak, "ms_per_step": tm,
+                                        "kernels": "gemm_* and flash_attention_*", "pass": "isolated" if src is iso else "as timed"}
+
+        # achievable HBM ceiling beside the published peak: the library's own plain copy
+        # kernel moving the master parameters (read + write = 8 bytes per parameter)
+        buf = torch.empty(stage.n_params, dtype=torch.float32, device=dev)
+        best = None
+        for _ in range(4):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            stage.amdp_stage_get_state(buf, None, None, None)
+            e1.record()
+            e1.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        del buf
+        copy_gbs = 8.0 * stage.n_params / best / 1e6
+        result["hbm_copy_ceiling"] = {"gbs": copy_gbs, "frac_of_hbm_peak": copy_gbs / PEAK_HBM_GBS,
+                                      "bytes": 8 * stage.n_params, "kernel": "copy16_kernel (amdp_stage_get_state)"}
+        for nm, row in result["streaming"].items():
+            row["frac_of_copy_ceiling"] = row["gbs"] / copy_gbs
+
+    # padded sequences (bidirectional blocks): tokens that are not padding, per second
+    if w.block_kind != 0 and not w.has_lm_head:
+        from tests.parity import aux_for
+        valid = 0
+        for i in range(n_warm, n_warm + K):
+            for kind, mb, ver in steps[i]:
+                if kind == amdp.EV_F:
+                    a = aux_for(w, mb % ring)
+                    valid += int(np.asarray(a[-w.microbatch:]).sum())
+        result["valid_tokens_per_s"] = valid / elapsed
 
     # ---- the same steps with the accumulation fused into backward (an option of
     # the library; `value` above is the schedule's own order) --------------------

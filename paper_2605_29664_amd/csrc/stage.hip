@@ -299,7 +299,7 @@ int device_copy(hipStream_t stream, void* dst, const void* src, size_t bytes) {
     if (!bytes) return AMDP_OK;
     if ((((uintptr_t)dst | (uintptr_t)src) & 15) == 0 && bytes % 16 == 0) {
         const long n16 = (long)(bytes / 16);
-        hipLaunchKernelGGL(copy16_kernel, dim3(stream_grid(n16)), dim3(STREAM_BLOCK), 0, stream, (u32x4*)dst,
+        hipLaunchKernelGGL(copy16_kernel, dim3(direct_grid(n16, ACC_BLOCK)), dim3(ACC_BLOCK), 0, stream, (u32x4*)dst,
                            (const u32x4*)src, n16);
     } else {
         if ((((uintptr_t)dst | (uintptr_t)src) & 3) || bytes % 4) return AMDP_E_INVAL;
@@ -313,7 +313,7 @@ int device_copy(hipStream_t stream, void* dst, const void* src, size_t bytes) {
 int device_zero(hipStream_t stream, void* dst, size_t bytes) {
     if (!bytes) return AMDP_OK;
     const long n16 = (long)(bytes / 16);
-    hipLaunchKernelGGL(zero16_kernel, dim3(stream_grid(n16)), dim3(STREAM_BLOCK), 0, stream, (u32x4*)dst, n16);
+    hipLaunchKernelGGL(zero16_kernel, dim3(direct_grid(n16, ACC_BLOCK)), dim3(ACC_BLOCK), 0, stream, (u32x4*)dst, n16);
     return after_launch();
 }
 

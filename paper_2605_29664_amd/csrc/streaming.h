@@ -103,25 +103,24 @@ __global__ __launch_bounds__(STREAM_BLOCK) void publish_kernel(const float* __re
 // memcpy/memset so that every byte the library moves is moved by a kernel that
 // is ordered on the stage's stream like all its other work. n16 = number of
 // 16-byte units.
-__global__ __launch_bounds__(STREAM_BLOCK) void copy16_kernel(u32x4* __restrict__ dst,
-                                                              const u32x4* __restrict__ src, long n16) {
-    const long stride = (long)gridDim.x * STREAM_BLOCK;
-    long i = (long)blockIdx.x * STREAM_BLOCK + threadIdx.x;
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-        dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
-    }
-    for (; i < n16; i += stride) dst[i] = src[i];
+// One 16-byte vector per lane, 64-lane workgroups, streaming loads and stores:
+// the launch shape that measured fastest for the accumulation as well.
+__global__ __launch_bounds__(ACC_BLOCK) void copy16_kernel(u32x4* __restrict__ dst,
+                                                           const u32x4* __restrict__ src, long n16) {
+    const long i = (long)blockIdx.x * ACC_BLOCK + threadIdx.x;
+    if (i >= n16) return;
+    __builtin_nontemporal_store(__builtin_nontemporal_load(&src[i]), &dst[i]);
 }
 __global__ __launch_bounds__(STREAM_BLOCK) void copy4_kernel(uint32_t* __restrict__ dst,
                                                              const uint32_t* __restrict__ src, long n4b) {
     const long stride = (long)gridDim.x * STREAM_BLOCK;
     for (long i = (long)blockIdx.x * STREAM_BLOCK + threadIdx.x; i < n4b; i += stride) dst[i] = src[i];
 }
-__global__ __launch_bounds__(STREAM_BLOCK) void zero16_kernel(u32x4* __restrict__ dst, long n16) {
-    const long stride = (long)gridDim.x * STREAM_BLOCK;
+__global__ __launch_bounds__(ACC_BLOCK) void zero16_kernel(u32x4* __restrict__ dst, long n16) {
+    const long i = (long)blockIdx.x * ACC_BLOCK + threadIdx.x;
+    if (i >= n16) return;
     const u32x4 z = {0u, 0u, 0u, 0u};
-    for (long i = (long)blockIdx.x * STREAM_BLOCK + threadIdx.x; i < n16; i += stride) dst[i] = z;
+    dst[i] = z;
 }
 
 // grid for the grid-stride helpers (copy, zero, publish)
