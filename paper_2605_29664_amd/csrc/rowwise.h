@@ -308,23 +308,27 @@ __global__ __launch_bounds__(256) void ce_fwd_kernel(T* logits, const int32_t* _
     T* p = logits + row * ld;
     const int nv = (int)(ld / V);
     const int t = targets[row];
-    float mx = -INFINITY;
+    // maximum and sum of exponentials in ONE pass over the row: each lane keeps a
+    // running maximum and rescales its running sum whenever the maximum moves
+    float mx = -INFINITY, sum = 0.f, tl = 0.f;
     for (int c = lane; c * V < Vocab; c += WAVE) {
         float a[V];
         load_vec<T>(p + c * V, a);
+        float vm = mx;
 #pragma unroll
-        for (int i = 0; i < V; ++i) if (c * V + i < Vocab) mx = fmaxf(mx, a[i]);
-    }
-    mx = wave_max(mx);
-    float sum = 0.f, tl = 0.f;
-    for (int c = lane; c * V < Vocab; c += WAVE) {
-        float a[V];
-        load_vec<T>(p + c * V, a);
+        for (int i = 0; i < V; ++i) if (c * V + i < Vocab) vm = fmaxf(vm, a[i]);
+        sum *= (mx == vm) ? 1.f : __expf(mx - vm);   // first vector: exp(-inf) = 0 times a sum of 0
+        mx = vm;
 #pragma unroll
         for (int i = 0; i < V; ++i) if (c * V + i < Vocab) {
             sum += __expf(a[i] - mx);
             if (c * V + i == t) tl = a[i];
         }
+    }
+    {
+        const float wm = wave_max(mx);
+        sum *= (mx == -INFINITY) ? 0.f : __expf(mx - wm);   // a lane that saw no column contributes nothing
+        mx = wm;
     }
     sum = wave_sum(sum);
     tl = wave_sum(tl);

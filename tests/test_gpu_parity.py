@@ -231,6 +231,17 @@ def test_side_stream_on_off_bit_identical():
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("vocab", [5000, 17000])
+def test_lm_head_wide_vocabulary(vocab):
+    """Rows of logits many vectors long per lane (the cross-entropy kernel's
+    running maximum and rescaled sum), a last vector round that is not full,
+    padding columns behind the vocabulary."""
+    w = W.TINY["lmhead_tile"].with_(vocab=vocab, n_layers=1)
+    rep = run_parity(w, n_windows=1, verbose=False)
+    _report(f"lmhead_tile_vocab{vocab}", rep)
+    assert rep["ok"], worst_entries(rep)
+
+
 def test_caller_may_overwrite_dy_right_after_backward():
     """Gradient leaves keep running on the side stream after backward returns,
     and the first ones read the caller's dY: overwriting dY on the caller's
