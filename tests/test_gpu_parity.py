@@ -194,7 +194,10 @@ def test_unfused_attention_fallback(key):
 def test_side_stream_on_off_bit_identical():
     """A whole schedule enqueued back to back with no read in between (so the
     gradient leaves and the accumulations really run beside the main chain)
-    must end in exactly the state the single-stream order produces."""
+    must end in exactly the state the single-stream order produces. The 12
+    activation slots are the schedule's in-flight bound (inject limit 3, four
+    pipelines), so every forward reuses the slot that was freed last, whose
+    backward's gradient leaves may still be running."""
     import paper_2605_29664_amd as amdp
     from oracle.stage import Stage as OStage
     w = W.TINY["gpt_tile"].with_(depth=16, pipelines=4, stage=8, threshold=4, stash_slots=3, lr=1e-3)
