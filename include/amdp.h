@@ -23,8 +23,12 @@
  *   - All GPU work is enqueued on the HIP stream given at create time and is
  *     ordered by that stream. The library never synchronises; outputs are
  *     valid once the stream reaches them.
- *   - State checks happen before anything is enqueued: a call that returns an
- *     error has changed nothing.
+ *   - State checks happen before anything is enqueued: a call that returns a
+ *     state-machine or argument error (every code but AMDP_E_HIP) has changed
+ *     nothing. AMDP_E_HIP means a HIP call or a launch failed part-way: work
+ *     enqueued before it stays enqueued and the stage should be reloaded with
+ *     amdp_stage_set_state.
+ *   - The library reads no environment variables.
  *   - Structs start with `struct_size` = sizeof(the struct) as compiled by the
  *     caller; a mismatch is AMDP_E_INVAL.
  */
@@ -203,6 +207,12 @@ int amdp_system_simulate(const amdp_sim_params_t* params, amdp_sim_op_t* ops, si
 
 enum { AMDP_BLOCK_GPT_PRELN_CAUSAL = 0, AMDP_BLOCK_BERT_POSTLN_BIDIR = 1 };
 enum { AMDP_FP32 = 0, AMDP_BF16 = 1 };
+/* AMDP_ATTN_AUTO: the fused attention kernels (scores never reach HBM, one fp32
+ * log-sum-exp per query kept for backward) wherever the shape allows: bf16,
+ * seq_len a multiple of 128, even head dimension <= 128; the three-kernel form
+ * elsewhere. AMDP_ATTN_UNFUSED: always scores GEMM, masked softmax, P V GEMM with
+ * the probabilities [b*H, s, s] kept in the activation slot. */
+enum { AMDP_ATTN_AUTO = 0, AMDP_ATTN_UNFUSED = 1 };
 
 typedef struct amdp_stage_config_t {
     uint32_t struct_size;
@@ -223,6 +233,7 @@ typedef struct amdp_stage_config_t {
     int32_t has_embedding; /* first stage: the block input is E[token] + P[position] (token and learned
                               position embedding, V = vocab rows and s rows of D); excludes has_lm_head;
                               d_model <= 8192 */
+    int32_t attention;     /* AMDP_ATTN_*; fixes the workspace layout together with the other fields */
 } amdp_stage_config_t;
 
 typedef struct amdp_stage amdp_stage_t;
@@ -349,6 +360,38 @@ int amdp_stage_set_overlap(amdp_stage_t* stage, int32_t on);
 /* *on (host) <- 1 when the side stream is in use, else 0. */
 int amdp_stage_get_overlap(const amdp_stage_t* stage, int32_t* on);
 
+/* Copies the published weights of resident version `version` (Section 3.1: the
+ * version a forward or backward is assigned; Section 3.4: what the owner of a
+ * stage's parameters sends to its replicas after an update) to `out`: device,
+ * n_params elements of the stage dtype in the flat layout, room rounded up to a
+ * multiple of 4 bytes. AMDP_E_VERSION if it is not resident. Enqueued on the
+ * stage's stream. */
+int amdp_stage_read_version(amdp_stage_t* stage, uint32_t version, void* out);
+
+/* dst <- src, `bytes` bytes of device memory (both 4-byte aligned, bytes a
+ * multiple of 4; AMDP_E_INVAL otherwise), by the library's own streaming copy
+ * kernel on `hip_stream`. It is what the stage uses for every copy it makes
+ * (inputs into activation slots, state in and out), offered to callers that
+ * record their work in a HIP graph and want no memcpy nodes in it, and to
+ * measurements as the plain copy whose rate is the achievable HBM ceiling. */
+int amdp_device_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+
+/* Kernel-selection switches for tests and measurements; none changes what is
+ * computed beyond rounding order inside a product. Takes effect from the next
+ * call on.
+ *   AMDP_OPT_GEMM_TILE               0 = the library's choice (default); 256, 128, 64 or
+ *                                    BM*1000+BN (128064, 64128) force that matrix-core tile
+ *                                    where it divides the product's shape; -1 = generic kernel
+ *   AMDP_OPT_GEMM_TRANSPOSING_READS  1 (default) m/n-contiguous operands are read from LDS with
+ *                                    the transposing read; 0 element by element
+ *   AMDP_OPT_GEMM_DIRECT_TO_LDS      tiles loaded from global memory straight into LDS: 1 (default)
+ *                                    where measured faster, 0 never, 2 wherever the shape allows
+ *   AMDP_OPT_LAZY_JOIN               1 (default) a backward leaves its gradient leaves running on the
+ *                                    side stream; 0 it ends by joining them */
+enum { AMDP_OPT_GEMM_TILE = 0, AMDP_OPT_GEMM_TRANSPOSING_READS = 1, AMDP_OPT_GEMM_DIRECT_TO_LDS = 2,
+       AMDP_OPT_LAZY_JOIN = 3 };
+int amdp_stage_set_option(amdp_stage_t* stage, int32_t option, int32_t value);
+
 /* The input embedding of the first stage and the output projection of the last
  * are one tied parameter held twice; before the update their gradient sums must
  * be added. first: a stage with has_embedding, last: a stage with has_lm_head,
@@ -382,11 +425,15 @@ int amdp_stage_join(amdp_stage_t* stage);
 /* ------------------------------------------------------------------------
  * Measurement aid: per-kernel-class device time from HIP events recorded on
  * the stage's stream around every launch between begin and end. `flops` and
- * `bytes` are the ALGORITHMIC work of the launches (2MNK per GEMM, only
- * visible query/key pairs under the causal mask; 12 bytes per parameter for
- * the accumulation, 32 + sizeof(stage dtype) per parameter for the update).
- * Profiling inserts events into the stream: do not time throughput while on.
- * amdp_stage_profile_end synchronises the stream.
+ * `bytes` are the ALGORITHMIC work of the launches (2MNK per GEMM; fused
+ * attention forward 2 products, backward 4 (dV, dP, dK in one kernel, dQ in the
+ * other), recomputed scores not counted, only visible query/key pairs under the
+ * causal mask; 12 bytes per parameter for the accumulation, 32 + sizeof(stage
+ * dtype) per parameter for the update).
+ * Profiling inserts events into the streams: do not time throughput while on.
+ * amdp_stage_profile_end joins the stage's side stream and synchronises both
+ * streams; an event that still cannot be read is AMDP_E_HIP, never a silently
+ * shorter record.
  * ------------------------------------------------------------------------ */
 typedef struct amdp_profile_entry_t {
     char     name[48];

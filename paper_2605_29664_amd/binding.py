@@ -15,6 +15,8 @@ BWD_STASHED, BWD_CURRENT = 0, 1
 FLAG_LAST_USE, FLAG_PARTIAL_WINDOW = 1, 2
 BLOCK_GPT, BLOCK_BERT = 0, 1
 FP32, BF16 = 0, 1
+ATTN_AUTO, ATTN_UNFUSED = 0, 1
+OPT_GEMM_TILE, OPT_GEMM_TRANSPOSING_READS, OPT_GEMM_DIRECT_TO_LDS, OPT_LAZY_JOIN = 0, 1, 2, 3
 E_INVAL, E_MB_STATE, E_NO_SLOT, E_VERSION, E_STASH_FULL, E_HIP, E_CAPACITY = -1, -2, -3, -4, -5, -6, -7
 
 
@@ -66,7 +68,8 @@ class amdp_stage_config_t(C.Structure):
                 ("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ffn", C.c_int32),
                 ("seq_len", C.c_int32), ("microbatch", C.c_int32), ("dtype", C.c_int32),
                 ("has_lm_head", C.c_int32), ("vocab", C.c_int32), ("ln_eps", C.c_float),
-                ("act_slots", C.c_int32), ("stash_slots", C.c_int32), ("has_embedding", C.c_int32)]
+                ("act_slots", C.c_int32), ("stash_slots", C.c_int32), ("has_embedding", C.c_int32),
+                ("attention", C.c_int32)]
 
 
 class amdp_param_desc_t(C.Structure):
@@ -151,6 +154,9 @@ def lib():
         "amdp_stage_set_overlap": (C.c_int, [vp, i32]),
         "amdp_stage_get_overlap": (C.c_int, [vp, P(i32)]),
         "amdp_stage_join": (C.c_int, [vp]),
+        "amdp_stage_set_option": (C.c_int, [vp, i32, i32]),
+        "amdp_device_copy": (C.c_int, [vp, vp, sz, vp]),
+        "amdp_stage_read_version": (C.c_int, [vp, u32, vp]),
         "amdp_stage_set_fused_accumulate": (C.c_int, [vp, i32]),
         "amdp_tie_embedding_grads": (C.c_int, [vp, vp]),
         "amdp_stage_profile_begin": (C.c_int, [vp]),
@@ -170,7 +176,7 @@ EXPORTED = ["amdp_strerror", "amdp_last_hip_error", "amdp_schedule_generate", "a
             "amdp_stage_create", "amdp_stage_destroy", "amdp_stage_set_state", "amdp_stage_get_state",
             "amdp_stage_get_staged_grad", "amdp_stage_resident_versions", "amdp_stage_forward",
             "amdp_stage_backward", "amdp_grad_accumulate", "amdp_apply_update",
-            "amdp_stage_set_overlap", "amdp_stage_get_overlap", "amdp_stage_join", "amdp_stage_set_fused_accumulate", "amdp_tie_embedding_grads",
+            "amdp_stage_set_overlap", "amdp_stage_get_overlap", "amdp_stage_join", "amdp_stage_set_option", "amdp_device_copy", "amdp_stage_read_version", "amdp_stage_set_fused_accumulate", "amdp_tie_embedding_grads",
             "amdp_stage_profile_begin", "amdp_stage_profile_end"]
 
 
@@ -246,11 +252,23 @@ def amdp_tie_embedding_grads(first, last):
     _check(lib().amdp_tie_embedding_grads(first.handle, last.handle), "amdp_tie_embedding_grads")
 
 
+def amdp_device_copy(dst, src, nbytes=None, stream=None):
+    """dst, src: contiguous tensors on one device; copies nbytes (default: all of src)."""
+    import torch
+    n = src.numel() * src.element_size() if nbytes is None else nbytes
+    if n > dst.numel() * dst.element_size() or n > src.numel() * src.element_size():
+        raise ValueError("amdp_device_copy: buffer too small")
+    st = stream if stream is not None else torch.cuda.current_stream(src.device)
+    _check(lib().amdp_device_copy(_ptr(dst, device=src.device), _ptr(src), n, C.c_void_p(st.cuda_stream)),
+           "amdp_device_copy")
+
+
 def make_config(block_kind, n_layers, d_model, n_heads, d_ffn, seq_len, microbatch, dtype,
-                has_lm_head=False, vocab=0, ln_eps=1e-5, act_slots=4, stash_slots=1, has_embedding=False):
+                has_lm_head=False, vocab=0, ln_eps=1e-5, act_slots=4, stash_slots=1, has_embedding=False,
+                attention=ATTN_AUTO):
     return amdp_stage_config_t(C.sizeof(amdp_stage_config_t), block_kind, n_layers, d_model, n_heads,
                                d_ffn, seq_len, microbatch, dtype, int(bool(has_lm_head)), vocab, ln_eps,
-                               act_slots, stash_slots, int(bool(has_embedding)))
+                               act_slots, stash_slots, int(bool(has_embedding)), attention)
 
 
 def amdp_stage_n_params(cfg):
@@ -387,6 +405,15 @@ class Stage:
 
     def amdp_stage_set_fused_accumulate(self, on):
         _check(lib().amdp_stage_set_fused_accumulate(self.handle, int(bool(on))), "amdp_stage_set_fused_accumulate")
+
+    def amdp_stage_set_option(self, option, value):
+        _check(lib().amdp_stage_set_option(self.handle, option, value), "amdp_stage_set_option")
+
+    def amdp_stage_read_version(self, version, out):
+        """out: tensor of the stage dtype with at least n_params (+1 if odd) elements."""
+        need = self.n_params + (self.n_params & 1 if self.act_dtype == self.torch.bfloat16 else 0)
+        _check(lib().amdp_stage_read_version(self.handle, version, _ptr(out, self.act_dtype, need, self.device)),
+               "amdp_stage_read_version")
 
     def amdp_stage_join(self):
         _check(lib().amdp_stage_join(self.handle), "amdp_stage_join")

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 
 namespace amdp {
 
@@ -15,6 +16,21 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int WAVE = 64;
+
+// Host side: raises the dynamic-LDS limit of kernel Kern to `bytes` on the
+// current device, once per device (a kernel attribute belongs to the device's
+// copy of the code object). Threads that race here both set the same value.
+template <auto Kern>
+inline hipError_t allow_dynamic_lds(int bytes) {
+    static std::atomic<uint64_t> done{0};          // one bit per device ordinal
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute((const void*)Kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
 
 template <class T> __device__ __forceinline__ float to_f32(T v) { return (float)v; }
 template <class T> __device__ __forceinline__ T from_f32(float v) { return (T)v; }   // bf16: RNE

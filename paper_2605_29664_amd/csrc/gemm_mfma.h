@@ -27,9 +27,6 @@
 namespace amdp {
 
 constexpr int MF_BK = 64;
-#ifndef AMDP_GEMM_SCHED
-#define AMDP_GEMM_SCHED 1
-#endif
 
 // LDS pointers carry their address space so that every access is a ds_*
 // instruction with an immediate offset.
@@ -46,10 +43,7 @@ struct OperandTile {
     // LDS rows are padded so that consecutive rows start 16 bytes (k-contiguous
     // tile: 128-bit reads of 16 rows) or 64 bytes (transposing reads: half a
     // wave reads 4 rows x 64 bytes at a time) further round the 64 banks.
-#ifndef AMDP_KM_PAD
-#define AMDP_KM_PAD 32
-#endif
-    static constexpr int PAD = KM ? AMDP_KM_PAD : 8;
+    static constexpr int PAD = KM ? 32 : 8;
     static constexpr int ROWS = KM ? MF_BK : R;
     static constexpr int COLS = (KM ? R : MF_BK) + PAD;
     static constexpr int BYTES = ROWS * COLS * 2;
@@ -209,14 +203,12 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_kernel(GemmArgs g) {
     };
     // scheduling directive: NMF MFMAs, each followed by one LDS read while any remain
     auto interleave_reads = [&]() {
-#if AMDP_GEMM_SCHED
 #pragma unroll
         for (int t = 0; t < NMF; ++t) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             if (t < NDS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         if (NDS > NMF) __builtin_amdgcn_sched_group_barrier(0x100, NDS - NMF, 0);
-#endif
     };
 
     // Pipeline. Tile kt is multiplied out of LDS stage kt&1 in four k-steps.
@@ -259,7 +251,6 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_kernel(GemmArgs g) {
         pb += b_step;
         TA::load(ra, pa, a_pass);
         TB::load(rb, pb, b_pass);
-#if AMDP_GEMM_SCHED
         __builtin_amdgcn_sched_group_barrier(0x100, NDS, 0);
 #pragma unroll
         for (int t = 0; t < NMF; ++t) {
@@ -268,7 +259,6 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_kernel(GemmArgs g) {
         }
         if (NVM > NMF) __builtin_amdgcn_sched_group_barrier(0x200, NVM - NMF, 0);
         __builtin_amdgcn_sched_group_barrier(0x020, NVM, 0);
-#endif
         __syncthreads();
         load_frags(0, nxt, 0);
         mfma_step(1);
@@ -344,7 +334,6 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_kernel(GemmArgs g) {
         compute_tile(cur);
         TA::store(ra, sa + nxt);
         TB::store(rb, sb + nxt);
-#if AMDP_GEMM_SCHED
         __builtin_amdgcn_sched_group_barrier(0x100, NDS, 0);
         constexpr int NVM = TA::NV + TB::NV;
 #pragma unroll
@@ -367,7 +356,6 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_kernel(GemmArgs g) {
             if (t < NVM) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
         }
         if (NVM > NMF) __builtin_amdgcn_sched_group_barrier(0x200, NVM - NMF, 0);
-#endif
         __syncthreads();
     }
     if (nk > 0) {
@@ -440,13 +428,8 @@ template <int BM, int BN, bool A_KM, bool B_KM, bool TR, int WGN = 2>
 inline hipError_t launch_gemm_mfma_inst(const GemmArgs& g, hipStream_t st) {
     constexpr size_t lds = mfma_lds_bytes<BM, BN, A_KM, B_KM>();
     static_assert(lds <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
-    auto kern = gemm_mfma_kernel<BM, BN, A_KM, B_KM, TR, WGN>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    constexpr auto kern = gemm_mfma_kernel<BM, BN, A_KM, B_KM, TR, WGN>;
+    if (hipError_t e = allow_dynamic_lds<kern>((int)lds); e != hipSuccess) return e;
     dim3 grid((g.M / BM) * (g.N / BN), 1, g.batch);
     hipLaunchKernelGGL(kern, grid, dim3(128 * WGN), lds, st, g);
     return hipGetLastError();

@@ -283,13 +283,8 @@ template <int BM, int BN, bool A_KM, bool B_KM, int WGN, bool EDGE = false>
 inline hipError_t launch_gemm_mfma_dl(const GemmArgs& g, hipStream_t st) {
     constexpr size_t lds = 2 * (size_t)(BM + BN) * MF_BK * 2;
     static_assert(lds <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
-    auto kern = gemm_mfma_dl_kernel<BM, BN, A_KM, B_KM, WGN, EDGE>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    constexpr auto kern = gemm_mfma_dl_kernel<BM, BN, A_KM, B_KM, WGN, EDGE>;
+    if (hipError_t e = allow_dynamic_lds<kern>((int)lds); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN)), dim3(128 * WGN), lds, st, g);
     return hipGetLastError();
 }

@@ -13,6 +13,7 @@
 #include "rowwise.h"
 #include "streaming.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -80,6 +81,7 @@ bool make_dims(const amdp_stage_config_t* c, Dims* d) {
     if (c->block_kind != AMDP_BLOCK_GPT_PRELN_CAUSAL && c->block_kind != AMDP_BLOCK_BERT_POSTLN_BIDIR)
         return false;
     if (c->dtype != AMDP_FP32 && c->dtype != AMDP_BF16) return false;
+    if (c->attention != AMDP_ATTN_AUTO && c->attention != AMDP_ATTN_UNFUSED) return false;
     if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->d_ffn < 1 || c->seq_len < 1 ||
         c->microbatch < 1)
         return false;
@@ -125,14 +127,10 @@ struct Carve {
     SlotLayout slot;
 };
 
-// Fused attention is used whenever the shape allows it (AMDP_FLASH=0 in the
-// environment switches it off for comparison runs). With it, only the fp32
-// log-sum-exp per (sequence, head, query) is kept instead of the s x s
-// probabilities.
-inline int flash_mode() {
-    const char* e = getenv("AMDP_FLASH");
-    return e ? atoi(e) : 1;
-}
+// Fused attention is used whenever the shape allows it (the configuration's
+// `attention` field can ask for the three-kernel form instead). With it, only
+// the fp32 log-sum-exp per (sequence, head, query) is kept instead of the
+// s x s probabilities.
 // The fused attention kernels exist for head dimensions 64 and 128. Other even
 // head dimensions up to 128 run through them zero-padded: Q, K, V (and dO, O in
 // backward) are repacked head by head into scratch with the padded width, which
@@ -151,7 +149,7 @@ void carve(const Dims& d, const amdp_stage_config_t& c, Carve* w) {
     w->versions = take(w->version_bytes * (size_t)(c.stash_slots + 1));
 
     const size_t ND = (size_t)d.N * d.D * d.esz, NF = (size_t)d.N * d.F * d.esz;
-    const bool fused = flash_mode() == 1 && flash_shape_ok(d);
+    const bool fused = c.attention == AMDP_ATTN_AUTO && flash_shape_ok(d);
     const size_t PP = fused ? (size_t)d.b * d.H * d.s * 4 : (size_t)d.b * d.H * d.s * d.s * d.esz;
     {
         size_t so = 0;
@@ -254,7 +252,7 @@ struct amdp_stage {
     uint64_t free_counter = 0;
     bool overlap = true;
     bool fused_acc = false;        // backward adds parameter gradients into G directly
-    int flash = 1;          // fused attention: 1 on (default), 0 off, 2 test mode: run after the three-kernel path
+    bool flash = true;      // fused attention kernels (shape permitting); false: scores, softmax, probabilities in HBM
     hipEvent_t next_event() { ev_next = (ev_next + 1) % 16; return events[ev_next]; }
 
     template <class P = void> P* at(size_t off) const { return (P*)(base + off); }
@@ -500,13 +498,13 @@ inline bool flash_ok(const Dims& d) { return flash_shape_ok(d); }
 // Workgroups of 256 lanes of kernel Kern that the whole GPU holds at once.
 template <auto Kern>
 int resident_blocks(int n_cu) {
-    static int per_cu = 0;
-    if (!per_cu) {
-        int v = 0;
+    static std::atomic<int> per_cu{0};     // a property of the kernel's code: the same on every gfx950
+    int v = per_cu.load(std::memory_order_relaxed);
+    if (!v) {
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, Kern, 256, 0) != hipSuccess || v < 1) v = 1;
-        per_cu = v;
+        per_cu.store(v, std::memory_order_relaxed);
     }
-    return per_cu * n_cu;
+    return v * n_cu;
 }
 
 // dst[r][j][0..w_dst) = src[r][j][0..w_src) cut or zero-padded to w_dst, for
@@ -570,7 +568,7 @@ int flash_bwd_launch(amdp_stage* st, const void* dO, const void* qkv, const void
                                                   (const bf16*)dO, lse2, (const float*)delta, (bf16*)dqkv, valid, d.s, d.H, Dk, scale, \
                                                   d.b * d.H, resident_blocks<KERN<DH, C>>(st->n_cu))
     {
-        ProfScope ps(st, "flash_attention_bwd_dkdv", 4.0 * unit, 0.0);   // S, dP, dV, dK
+        ProfScope ps(st, "flash_attention_bwd_dkdv", 3.0 * unit, 0.0);   // dP, dV, dK (the recomputed S is not counted)
         if (dhk == 128) { if (d.causal) FLASH_BWD(flash_bwd_dkv_kernel, 128, true); else FLASH_BWD(flash_bwd_dkv_kernel, 128, false); }
         else { if (d.causal) FLASH_BWD(flash_bwd_dkv_kernel, 64, true); else FLASH_BWD(flash_bwd_dkv_kernel, 64, false); }
         TRY(after_launch());
@@ -604,7 +602,7 @@ int flash_bwd(amdp_stage* st, const void* dO, const void* qkv, const void* o, co
 template <class T>
 int attention_fwd(amdp_stage* st, const void* qkv_, void* P_, void* o_, const int32_t* valid) {
     const Dims& d = st->d;
-    if (st->flash == 1 && flash_ok(d)) return flash_fwd(st, qkv_, o_, (float*)P_, valid);
+    if (st->flash && flash_ok(d)) return flash_fwd(st, qkv_, o_, (float*)P_, valid);
     const T* qkv = (const T*)qkv_;
     const long ld3 = 3L * d.D;
     {   // S = Q K^T
@@ -634,8 +632,6 @@ int attention_fwd(amdp_stage* st, const void* qkv_, void* P_, void* o_, const in
         g.causal = d.causal ? 2 : 0;
         TRY(gemm(st, G_NN, g, d.s, ld3));
     }
-    if (st->flash == 2 && flash_ok(d))   // test mode: overwrite O with the fused kernel's result
-        TRY(flash_fwd(st, qkv_, o_, st->at<float>(st->w.dP), valid));
     return AMDP_OK;
 }
 
@@ -644,7 +640,7 @@ template <class T>
 int attention_bwd(amdp_stage* st, const void* dO_, const void* qkv_, const void* P_, const void* o_, void* dP_,
                   void* dqkv_, const int32_t* valid) {
     const Dims& d = st->d;
-    if (st->flash == 1 && flash_ok(d))
+    if (st->flash && flash_ok(d))
         return flash_bwd(st, dO_, qkv_, o_, (const float*)P_, (float*)dP_, dqkv_, valid);
     const T* qkv = (const T*)qkv_;
     T* dqkv = (T*)dqkv_;
@@ -1031,7 +1027,6 @@ extern "C" int amdp_stage_create(const amdp_stage_config_t* cfg, void* workspace
     }
     st->launch = st->stream;
     st->n_vslots = cfg->stash_slots + 1;
-    const char* ov = getenv("AMDP_OVERLAP");
     {
         bool ok = hip_ok(hipStreamCreateWithFlags(&st->side, hipStreamNonBlocking), "hipStreamCreateWithFlags");
         for (int i = 0; ok && i < 16; ++i)
@@ -1046,12 +1041,7 @@ extern "C" int amdp_stage_create(const amdp_stage_config_t* cfg, void* workspace
     // unit with a 256x256 tile, concurrent kernels only share the units (measured: no
     // gain at D = 4096, 3 % at 2048, 11 % at 1024), so it is off by default there.
     st->overlap = (long)(st->d.D / 256) * (st->d.D / 256) < st->n_cu;
-    if (ov) st->overlap = atoi(ov) != 0;
-    st->flash = flash_mode();
-    if (const char* e = getenv("AMDP_LAZY_JOIN")) st->lazy_join = atoi(e) != 0;
-    if (const char* e = getenv("AMDP_GEMM_TR")) st->use_tr = atoi(e) != 0;
-    if (const char* e = getenv("AMDP_GEMM_TILE")) st->force_tile = atoi(e);
-    if (const char* e = getenv("AMDP_GEMM_DIRECT")) st->use_direct = atoi(e);
+    st->flash = cfg->attention == AMDP_ATTN_AUTO;
     // parameter buffers, version slots and the padding behind them start at zero
     if (device_zero(st->launch, st->base, st->w.act) != AMDP_OK) {
         amdp_stage_destroy(st);
@@ -1260,8 +1250,11 @@ extern "C" int amdp_stage_profile_begin(amdp_stage_t* st) {
 extern "C" int amdp_stage_profile_end(amdp_stage_t* st, amdp_profile_entry_t* out, int32_t cap, int32_t* n) {
     if (!st || !n || !st->prof.on) return AMDP_E_INVAL;
     st->prof.on = false;
-    int rc = AMDP_OK;
-    if (hipStreamSynchronize(st->stream) != hipSuccess) rc = AMDP_E_HIP;
+    // gradient leaves and accumulations carry their events on the side stream:
+    // order it before the caller's stream, then wait for both
+    int rc = join_leaves(st);
+    if (rc == AMDP_OK && !hip_ok(hipStreamSynchronize(st->stream), "hipStreamSynchronize")) rc = AMDP_E_HIP;
+    if (rc == AMDP_OK && st->side && !hip_ok(hipStreamSynchronize(st->side), "hipStreamSynchronize(side)")) rc = AMDP_E_HIP;
     std::vector<amdp_profile_entry_t> agg(st->prof.names.size());
     for (size_t i = 0; i < agg.size(); ++i) {
         memset(&agg[i], 0, sizeof(agg[i]));
@@ -1269,9 +1262,13 @@ extern "C" int amdp_stage_profile_end(amdp_stage_t* st, amdp_profile_entry_t* ou
     }
     for (ProfRecord& r : st->prof.recs) {
         float ms = 0.f;
-        if (rc == AMDP_OK && hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
-            amdp_profile_entry_t& e = agg[r.name_id];
-            e.launches += 1; e.ms += ms; e.flops += r.flops; e.bytes += r.bytes;
+        if (rc == AMDP_OK) {
+            if (hip_ok(hipEventElapsedTime(&ms, r.start, r.stop), "hipEventElapsedTime")) {
+                amdp_profile_entry_t& e = agg[r.name_id];
+                e.launches += 1; e.ms += ms; e.flops += r.flops; e.bytes += r.bytes;
+            } else {
+                rc = AMDP_E_HIP;      // an event that is not complete after both waits: report, do not undercount
+            }
         }
         hipEventDestroy(r.start);
         hipEventDestroy(r.stop);
@@ -1297,6 +1294,40 @@ extern "C" int amdp_tie_embedding_grads(amdp_stage_t* first, amdp_stage_t* last)
                        first->at<float>(first->w.G) + first->d.off_tok(),
                        last->at<float>(last->w.G) + last->d.off_embed(), n4);
     return after_launch();
+}
+
+extern "C" int amdp_device_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+    if (bytes && (!dst || !src)) return AMDP_E_INVAL;
+    return device_copy((hipStream_t)hip_stream, dst, src, bytes);
+}
+
+extern "C" int amdp_stage_set_option(amdp_stage_t* st, int32_t option, int32_t value) {
+    if (!st) return AMDP_E_INVAL;
+    switch (option) {
+        case AMDP_OPT_GEMM_TILE:
+            st->force_tile = value;
+            return AMDP_OK;
+        case AMDP_OPT_GEMM_TRANSPOSING_READS:
+            st->use_tr = value != 0;
+            return AMDP_OK;
+        case AMDP_OPT_GEMM_DIRECT_TO_LDS:
+            if (value < 0 || value > 2) return AMDP_E_INVAL;
+            st->use_direct = value;
+            return AMDP_OK;
+        case AMDP_OPT_LAZY_JOIN:
+            TRY(join_leaves(st));
+            st->lazy_join = value != 0;
+            return AMDP_OK;
+    }
+    return AMDP_E_INVAL;
+}
+
+extern "C" int amdp_stage_read_version(amdp_stage_t* st, uint32_t version, void* out) {
+    if (!st || !out) return AMDP_E_INVAL;
+    const int slot = st->find_version(version);
+    if (slot < 0) return AMDP_E_VERSION;
+    if ((uintptr_t)out % 4) return AMDP_E_INVAL;
+    return device_copy(st->launch, out, st->version_ptr(slot), round_up((size_t)st->d.n_params() * st->d.esz, 4));
 }
 
 extern "C" int amdp_stage_set_fused_accumulate(amdp_stage_t* st, int32_t on) {

@@ -38,3 +38,12 @@ def test_more_than_one_gpu_is_refused_with_a_message():
                        timeout=120)
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_default_workload_is_the_largest_configuration_and_nothing_comes_from_tests():
+    src = open(os.path.join(ROOT, "bench.py")).read()
+    assert 'default="5"' in src
+    assert "from tests" not in src and "import tests" not in src
+    # the oracle is imported inside cpu_baseline() only
+    head, tail = src.split("def cpu_baseline", 1)
+    assert "oracle" not in head.replace("CPU oracle", "").replace("the oracle", "") and "from oracle" in tail

@@ -7,8 +7,8 @@ lives here, and it imports neither the oracle nor the HIP binding.
 """
 from .configs import StageWorkload, CONFIGS, TINY, PAPER, FIRST, get
 from .gen import (quantize_bf16_grid, make_theta, make_x, make_dy,
-                  make_valid_len, make_targets, make_tokens, seed_for)
+                  make_valid_len, make_targets, make_tokens, make_aux, stage_config_args, seed_for)
 
 __all__ = ["StageWorkload", "CONFIGS", "TINY", "PAPER", "FIRST", "get", "quantize_bf16_grid",
            "make_theta", "make_x", "make_dy", "make_valid_len", "make_targets", "make_tokens",
-           "seed_for"]
+           "make_aux", "stage_config_args", "seed_for"]

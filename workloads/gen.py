@@ -9,7 +9,7 @@ seed = 296640 + config number + 1000 * buffer index.
 """
 import numpy as np
 
-from .configs import BF16
+from .configs import BF16, BERT_POSTLN_BIDIR
 
 SEED_BASE = 29664 * 10
 
@@ -75,3 +75,29 @@ def make_tokens(workload, mb):
     """Token ids of a first-stage minibatch, uniform over the vocabulary."""
     rng = np.random.default_rng(seed_for(workload, 900000 + mb))
     return rng.integers(0, workload.vocab, size=workload.tokens).astype(np.int32)
+
+
+def make_aux(workload, mb):
+    """The int32 side input of a forward: targets on an LM-head stage; token
+    ids (then the padding mask of a bidirectional block) on a first stage; the
+    padding mask alone for other bidirectional stages; else None."""
+    if workload.has_lm_head:
+        return make_targets(workload, mb)
+    if workload.has_embedding:
+        t = make_tokens(workload, mb)
+        return np.concatenate([t, make_valid_len(workload, mb)]) if workload.block_kind == BERT_POSTLN_BIDIR else t
+    if workload.block_kind == BERT_POSTLN_BIDIR:
+        return make_valid_len(workload, mb)
+    return None
+
+
+def stage_config_args(workload, **overrides):
+    """Keyword arguments that describe `workload` as a stage configuration
+    (field names of the library's configuration record), as a plain dict."""
+    args = dict(block_kind=workload.block_kind, n_layers=workload.n_layers, d_model=workload.d_model,
+                n_heads=workload.n_heads, d_ffn=workload.d_ffn, seq_len=workload.seq_len,
+                microbatch=workload.microbatch, dtype=workload.dtype, has_lm_head=workload.has_lm_head,
+                vocab=workload.vocab, ln_eps=workload.ln_eps, act_slots=workload.act_slots,
+                stash_slots=workload.stash_slots, has_embedding=workload.has_embedding)
+    args.update(overrides)
+    return args
