@@ -5,7 +5,7 @@ result event by event. Used by the GPU tests and by __graft_entry__.smoke().
 Two gates per compared tensor (Y, dX, every parameter's slice of g, G, m, v,
 theta, the loss):
   * norm-wise   ||x - ref||_F / ||ref||_F        <= TOL[dtype]
-  * element-wise max|x - ref| / rms(ref)         <= ELEM_TOL[dtype]
+  * element-wise max|x - ref| / rms(ref != 0)    <= ELEM_TOL[dtype]
 The second one is there so that a few wrong rows or a wrong last tile cannot
 hide inside the norm of a large tensor: one entry that is off by the tensor's
 own typical magnitude fails it.
@@ -14,7 +14,8 @@ At every update the library's Adam step is also checked against the oracle's
 step applied to the LIBRARY's own state before the update (same G, m, v, theta
 in, so no bf16 noise enters): the change of theta must agree to 1e-3, m and v
 to 1e-6, and the published 16-bit version must be the round-to-nearest-even of
-the new master bit for bit."""
+the new master bit for bit. (theta against the free-running oracle is compared
+norm-wise over the whole vector only; see the comment at the update.)"""
 import os
 import sys
 import time
@@ -36,9 +37,13 @@ TOL = {W.configs.BF16: 2e-2, W.configs.FP32: 1e-5}
 # element-wise: max |x - ref| <= ELEM_TOL * rms(ref). bf16: an output of typical size rms is
 # rounded to 8 bits (relative 2^-9 = 2e-3 each, the largest entries of a normal-like tensor are
 # ~5 rms, so rounding alone reaches 1e-2 rms) and its inputs carry the same rounding through
-# products of hundreds to thousands of terms; measured maxima over all test shapes stay below
-# 0.12, a single entry replaced by another entry of the tensor gives ~1.4.
-ELEM_TOL = {W.configs.BF16: 0.25, W.configs.FP32: 2e-4}
+# products of hundreds to thousands of terms; measured maxima over all test shapes and the five
+# configurations at full depth: 0.19 (bf16), 1.9e-5 (fp32). An entry replaced by an unrelated
+# one is off by ~1.4 rms on average, and the largest of a wrong row's entries by 3 rms or more.
+# rms is taken over the entries of ref that are not exactly zero, so that a tensor that is zero
+# by structure almost everywhere (the token embedding's gradient) is measured in units of its
+# populated entries.
+ELEM_TOL = {W.configs.BF16: 0.5, W.configs.FP32: 2e-4}
 # Adam step with identical inputs on both sides (fp32 kernel against the fp64 oracle)
 UPDATE_SAME_INPUT_TOL = dict(delta_theta=1e-3, moments=1e-6)
 
@@ -54,12 +59,12 @@ def rel_err(x, ref):
 
 
 def elem_err(x, ref):
-    """max |x - ref| in units of rms(ref)."""
+    """max |x - ref| in units of the rms of ref's non-zero entries."""
     x = np.asarray(x, dtype=np.float64).reshape(-1)
     ref = np.asarray(ref, dtype=np.float64).reshape(-1)
     if ref.size == 0:
         return 0.0
-    rms = float(np.sqrt(np.mean(ref * ref)))
+    rms = float(np.sqrt(np.sum(ref * ref) / max(1, np.count_nonzero(ref))))
     num = float(np.max(np.abs(x - ref)))
     if not np.isfinite(num):
         return float("inf")
@@ -231,8 +236,17 @@ def run_parity(w, n_windows=2, policy=OSched.STASHED, placement=OSched.NEXT_BUBB
             orun.update()
             nv = gpu.update(w, 1.0 / T)
             s = gpu.state()
-            for key in ("m", "v", "theta"):
-                note_slices(ev, key + ".", s[key], getattr(orun, key))
+            note_slices(ev, "m.", s["m"], orun.m)
+            # v is the square of the gradient: its largest entries are many rms of v, and an
+            # error of the gradient is multiplied by them; norm-wise only (element-wise the
+            # gradient sum itself is gated at every accumulation, v's arithmetic just below)
+            note_slices(ev, "v.", s["v"], orun.v, gate_tol=(tol, None))
+            # theta against the free-running oracle over the whole vector, norm-wise only: Adam
+            # divides by |g|, so where a gradient is zero up to rounding noise (the key bias:
+            # softmax ignores a constant added to a row of scores) both sides step by lr times a
+            # random sign, which is noise of size lr in that slice and says nothing about the
+            # kernel. What pins the update itself is the same-input comparison below.
+            note(ev, "theta", s["theta"], orun.theta, gate_tol=(tol, None))
             # the kernel's step against the oracle's step from the library's own state
             th, m_, v_ = OOptim.adam_step(s0["theta"].astype(np.float64), s0["m"].astype(np.float64),
                                           s0["v"].astype(np.float64), s0["G"].astype(np.float64), s0["step"] + 1,
