@@ -368,6 +368,44 @@ int amdp_stage_get_overlap(const amdp_stage_t* stage, int32_t* on);
  * stage's stream. */
 int amdp_stage_read_version(amdp_stage_t* stage, uint32_t version, void* out);
 
+/* ------------------------------------------------------------------------
+ * Row operators of the transformer block (Section 4.1, Table 2: GPT- and
+ * BERT-style layers, each with two LayerNorms and a bias on every linear map),
+ * callable on their own on caller-owned device buffers. They are the kernels the
+ * stage itself launches; they exist as entry points so that each can be checked
+ * and timed in isolation. Matrices are row-major [rows, cols] in `dtype`
+ * (AMDP_FP32 / AMDP_BF16), 16-byte aligned, cols a multiple of 4 (fp32) or 8
+ * (bf16); rows may be 0. All work is enqueued on `hip_stream`; nothing
+ * synchronises. AMDP_E_INVAL on a bad shape, type, alignment or null pointer.
+ * ------------------------------------------------------------------------ */
+
+/* y = (x - mean) * rstd * gamma + beta per row, biased variance, rstd =
+ * 1/sqrt(var + eps), statistics in fp32; stats[2r] = mean, stats[2r+1] = rstd
+ * (device fp32 [rows, 2]) are what the backward operators take. gamma, beta:
+ * device [cols] in `dtype`. */
+int amdp_layernorm_forward(const void* x, const void* gamma, const void* beta, void* y, float* stats,
+                           int32_t rows, int32_t cols, int32_t dtype, float eps, void* hip_stream);
+
+/* dx = (res +) rstd * (g - mean_row(g) - xhat * mean_row(g * xhat)) with g = dy *
+ * gamma and xhat = (x - mean) * rstd from `stats`; res (may be NULL) is a
+ * residual-branch gradient added in the same pass. dx may alias dy or res. */
+int amdp_layernorm_backward(const void* dy, const void* x, const float* stats, const void* gamma,
+                            const void* res, void* dx, int32_t rows, int32_t cols, int32_t dtype,
+                            void* hip_stream);
+
+/* Parameter gradients that are column sums over the tokens, in fp32, in two
+ * deterministic stages (no float atomics: bit-identical run to run):
+ *   x == NULL: out[c] = sum_r dy[r][c], c < cols             (bias gradient)
+ *   x != NULL: out[c] = sum_r dy[r][c] * xhat[r][c]          (LayerNorm gain)
+ *              out[cols + c] = sum_r dy[r][c]                (LayerNorm bias)
+ *              with xhat from x and `stats` as above
+ * out: device fp32 [cols] or [2*cols]. workspace: device, 16-byte aligned, at
+ * least amdp_column_sums_workspace_bytes(...) bytes (0 = invalid arguments); it
+ * holds the first stage's partial sums and needs no initialisation. */
+size_t amdp_column_sums_workspace_bytes(int32_t rows, int32_t cols, int32_t dtype, int32_t with_layernorm);
+int amdp_column_sums(const void* dy, const void* x, const float* stats, float* out, int32_t rows,
+                     int32_t cols, int32_t dtype, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* dst <- src, `bytes` bytes of device memory (both 4-byte aligned, bytes a
  * multiple of 4; AMDP_E_INVAL otherwise), by the library's own streaming copy
  * kernel on `hip_stream`. It is what the stage uses for every copy it makes

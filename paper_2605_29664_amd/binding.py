@@ -156,6 +156,10 @@ def lib():
         "amdp_stage_join": (C.c_int, [vp]),
         "amdp_stage_set_option": (C.c_int, [vp, i32, i32]),
         "amdp_device_copy": (C.c_int, [vp, vp, sz, vp]),
+        "amdp_layernorm_forward": (C.c_int, [vp, vp, vp, vp, vp, i32, i32, i32, C.c_float, vp]),
+        "amdp_layernorm_backward": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i32, i32, vp]),
+        "amdp_column_sums_workspace_bytes": (sz, [i32, i32, i32, i32]),
+        "amdp_column_sums": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, vp, sz, vp]),
         "amdp_stage_read_version": (C.c_int, [vp, u32, vp]),
         "amdp_stage_set_fused_accumulate": (C.c_int, [vp, i32]),
         "amdp_tie_embedding_grads": (C.c_int, [vp, vp]),
@@ -176,7 +180,8 @@ EXPORTED = ["amdp_strerror", "amdp_last_hip_error", "amdp_schedule_generate", "a
             "amdp_stage_create", "amdp_stage_destroy", "amdp_stage_set_state", "amdp_stage_get_state",
             "amdp_stage_get_staged_grad", "amdp_stage_resident_versions", "amdp_stage_forward",
             "amdp_stage_backward", "amdp_grad_accumulate", "amdp_apply_update",
-            "amdp_stage_set_overlap", "amdp_stage_get_overlap", "amdp_stage_join", "amdp_stage_set_option", "amdp_device_copy", "amdp_stage_read_version", "amdp_stage_set_fused_accumulate", "amdp_tie_embedding_grads",
+            "amdp_stage_set_overlap", "amdp_stage_get_overlap", "amdp_stage_join", "amdp_stage_set_option", "amdp_device_copy", "amdp_layernorm_forward", "amdp_layernorm_backward",
+            "amdp_column_sums_workspace_bytes", "amdp_column_sums", "amdp_stage_read_version", "amdp_stage_set_fused_accumulate", "amdp_tie_embedding_grads",
             "amdp_stage_profile_begin", "amdp_stage_profile_end"]
 
 
@@ -261,6 +266,60 @@ def amdp_device_copy(dst, src, nbytes=None, stream=None):
     st = stream if stream is not None else torch.cuda.current_stream(src.device)
     _check(lib().amdp_device_copy(_ptr(dst, device=src.device), _ptr(src), n, C.c_void_p(st.cuda_stream)),
            "amdp_device_copy")
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return FP32
+    raise TypeError(f"unsupported element type {t.dtype}")
+
+
+def _stream_ptr(t, stream):
+    import torch
+    st = stream if stream is not None else torch.cuda.current_stream(t.device)
+    return C.c_void_p(st.cuda_stream)
+
+
+def amdp_layernorm_forward(x, gamma, beta, y, stats, eps, stream=None):
+    """x, y: [rows, cols]; gamma, beta: [cols]; stats: float32 [rows, 2]."""
+    import torch
+    rows, cols = x.shape
+    dev, dt = x.device, x.dtype
+    _check(lib().amdp_layernorm_forward(_ptr(x), _ptr(gamma, dt, cols, dev), _ptr(beta, dt, cols, dev),
+                                        _ptr(y, dt, rows * cols, dev), _ptr(stats, torch.float32, 2 * rows, dev),
+                                        rows, cols, _dtype_code(x), eps, _stream_ptr(x, stream)),
+           "amdp_layernorm_forward")
+
+
+def amdp_layernorm_backward(dy, x, stats, gamma, res, dx, stream=None):
+    import torch
+    rows, cols = x.shape
+    dev, dt = x.device, x.dtype
+    _check(lib().amdp_layernorm_backward(_ptr(dy, dt, rows * cols, dev), _ptr(x), _ptr(stats, torch.float32, 2 * rows, dev),
+                                         _ptr(gamma, dt, cols, dev), _ptr(res, dt, rows * cols, dev),
+                                         _ptr(dx, dt, rows * cols, dev), rows, cols, _dtype_code(x),
+                                         _stream_ptr(x, stream)), "amdp_layernorm_backward")
+
+
+def amdp_column_sums_workspace_bytes(rows, cols, dtype, with_layernorm):
+    return lib().amdp_column_sums_workspace_bytes(rows, cols, dtype, int(bool(with_layernorm)))
+
+
+def amdp_column_sums(dy, x, stats, out, workspace, stream=None):
+    """dy: [rows, cols]; x, stats: None for plain column sums (out float32 [cols]),
+    else the LayerNorm input and statistics (out float32 [2*cols]); workspace: uint8 tensor."""
+    import torch
+    rows, cols = dy.shape
+    dev = dy.device
+    ln = x is not None
+    _check(lib().amdp_column_sums(_ptr(dy), _ptr(x, dy.dtype, rows * cols, dev),
+                                  _ptr(stats, torch.float32, 2 * rows, dev) if ln else None,
+                                  _ptr(out, torch.float32, (2 if ln else 1) * cols, dev), rows, cols, _dtype_code(dy),
+                                  _ptr(workspace, torch.uint8, None, dev), workspace.numel(), _stream_ptr(dy, stream)),
+           "amdp_column_sums")
 
 
 def make_config(block_kind, n_layers, d_model, n_heads, d_ffn, seq_len, microbatch, dtype,

@@ -447,43 +447,66 @@ int gemm(amdp_stage* st, GemmLayout lay, GemmArgs g, long lda, long ldb) {
 
 // ---- typed launch helpers ---------------------------------------------------
 template <class T>
+int launch_ln_fwd(hipStream_t s, const void* x, const void* gamma, const void* beta, void* y, float* stats, int N,
+                  int D, float eps) {
+    hipLaunchKernelGGL(ln_fwd_kernel<T>, dim3((N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0, s,
+                       (const T*)x, (const T*)gamma, (const T*)beta, (T*)y, stats, N, D, eps);
+    return after_launch();
+}
+template <class T>
+int launch_ln_bwd(hipStream_t s, const void* dy, const void* x, const float* stats, const void* gamma,
+                  const void* res, void* dx, int N, int D) {
+    hipLaunchKernelGGL(ln_bwd_kernel<T>, dim3((N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0, s,
+                       (const T*)dy, (const T*)x, stats, (const T*)gamma, (const T*)res, (T*)dx, N, D);
+    return after_launch();
+}
+template <class T>
 int ln_fwd(amdp_stage* st, const void* x, const void* gamma, const void* beta, void* y, float* stats) {
     const Dims& d = st->d;
     ProfScope ps(st, "layernorm_fwd", 0.0, (double)d.N * d.D * sizeof(T) * 2);
-    hipLaunchKernelGGL(ln_fwd_kernel<T>, dim3((d.N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0,
-                       st->launch, (const T*)x, (const T*)gamma, (const T*)beta, (T*)y, stats, d.N, d.D,
-                       st->cfg.ln_eps);
-    return after_launch();
+    return launch_ln_fwd<T>(st->launch, x, gamma, beta, y, stats, d.N, d.D, st->cfg.ln_eps);
 }
 template <class T>
 int ln_bwd(amdp_stage* st, const void* dy, const void* x, const float* stats, const void* gamma,
            const void* res, void* dx) {
     const Dims& d = st->d;
     ProfScope ps(st, "layernorm_bwd", 0.0, (double)d.N * d.D * sizeof(T) * (res ? 4 : 3));
-    hipLaunchKernelGGL(ln_bwd_kernel<T>, dim3((d.N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0,
-                       st->launch, (const T*)dy, (const T*)x, stats, (const T*)gamma, (const T*)res, (T*)dx,
-                       d.N, d.D);
-    return after_launch();
+    return launch_ln_bwd<T>(st->launch, dy, x, stats, gamma, res, dx, d.N, d.D);
+}
+
+// Column sums in two deterministic stages through `partial` (fp32 [chunks][width]).
+// The split of the rows: enough chunks to put ~4 blocks on every compute unit, at
+// least 8 rows each, at most max_chunks (what `partial` has room for).
+struct ColSumPlan { int col_blocks, chunks, rows_per_chunk; };
+inline ColSumPlan plan_column_sums(int N, int C, int vec, int n_cu, int max_chunks) {
+    ColSumPlan p;
+    p.col_blocks = (C + 64 * vec - 1) / (64 * vec);
+    int chunks = std::min(max_chunks, std::max(1, 4 * n_cu / p.col_blocks));
+    p.rows_per_chunk = std::max(8, (N + chunks - 1) / chunks);
+    p.chunks = (N + p.rows_per_chunk - 1) / p.rows_per_chunk;
+    return p;
 }
 // out[0..C) = column sums of dy [N, C]; with LN: out[0..C) = sum dy*xhat, out[C..2C) = sum dy
 template <class T, bool LN>
+int launch_column_sums(hipStream_t s, const void* dy, const void* x, const float* stats, float* partial, float* out,
+                       int N, int C, const ColSumPlan& p, int accumulate) {
+    if (p.chunks > 0) {      // no rows: the second stage alone writes zeros
+        hipLaunchKernelGGL((colreduce_partial_kernel<T, LN>), dim3(p.col_blocks, p.chunks), dim3(256), 0, s,
+                           (const T*)dy, (const T*)x, stats, partial, N, C, p.rows_per_chunk);
+        TRY(after_launch());
+    }
+    const int width = LN ? 2 * C : C;
+    hipLaunchKernelGGL(colreduce_final_kernel, dim3((width + 15) / 16), dim3(256), 0, s, partial, out, width,
+                       p.chunks, accumulate);
+    return after_launch();
+}
+template <class T, bool LN>
 int colreduce(amdp_stage* st, const void* dy, const void* x, const float* stats, float* out, int C) {
     const Dims& d = st->d;
-    // enough row chunks to put ~4 blocks on every compute unit, at least 8 rows each
-    constexpr int V = Vec<T>::N;
-    const int col_blocks = (C + 64 * V - 1) / (64 * V);
-    int chunks = std::min(st->w.partial_chunks, std::max(1, 4 * st->n_cu / col_blocks));
-    int rpc = std::max(8, (d.N + chunks - 1) / chunks);
-    chunks = (d.N + rpc - 1) / rpc;
-    float* partial = st->at<float>(st->w.partial);
+    const ColSumPlan p = plan_column_sums(d.N, C, Vec<T>::N, st->n_cu, st->w.partial_chunks);
     ProfScope ps(st, LN ? "colreduce_ln" : "colreduce_bias", 0.0, (double)d.N * C * sizeof(T) * (LN ? 2 : 1));
-    hipLaunchKernelGGL((colreduce_partial_kernel<T, LN>), dim3(col_blocks, chunks), dim3(256), 0,
-                       st->launch, (const T*)dy, (const T*)x, stats, partial, d.N, C, rpc);
-    TRY(after_launch());
-    const int width = LN ? 2 * C : C;
-    hipLaunchKernelGGL(colreduce_final_kernel, dim3((width + 15) / 16), dim3(256), 0, st->launch, partial,
-                       out, width, chunks, st->fused_acc ? 1 : 0);
-    return after_launch();
+    return launch_column_sums<T, LN>(st->launch, dy, x, stats, st->at<float>(st->w.partial), out, d.N, C, p,
+                                     st->fused_acc ? 1 : 0);
 }
 
 GemmArgs attn_batch(const Dims& d) {
@@ -1294,6 +1317,78 @@ extern "C" int amdp_tie_embedding_grads(amdp_stage_t* first, amdp_stage_t* last)
                        first->at<float>(first->w.G) + first->d.off_tok(),
                        last->at<float>(last->w.G) + last->d.off_embed(), n4);
     return after_launch();
+}
+
+// ---- row operators of the block, callable on their own ---------------------------
+namespace {
+int device_cu_count() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        cus = 256;
+    return cus;
+}
+// rows x cols of `dtype`, 16-byte vectors along a row
+bool row_op_shape_ok(int32_t rows, int32_t cols, int32_t dtype) {
+    if (dtype != AMDP_FP32 && dtype != AMDP_BF16) return false;
+    if (rows < 0 || cols < 1) return false;
+    return cols % (dtype == AMDP_BF16 ? 8 : 4) == 0;
+}
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+constexpr int COLSUM_MAX_CHUNKS = 256;
+
+int column_sums_impl(const void* dy, const void* x, const float* stats, float* out, int32_t rows, int32_t cols,
+                     int32_t dtype, float* partial, int max_chunks, hipStream_t s) {
+    const bool ln = x != nullptr;
+    const ColSumPlan p = plan_column_sums(rows, cols, dtype == AMDP_BF16 ? 8 : 4, device_cu_count(), max_chunks);
+    if (dtype == AMDP_BF16)
+        return ln ? launch_column_sums<bf16, true>(s, dy, x, stats, partial, out, rows, cols, p, 0)
+                  : launch_column_sums<bf16, false>(s, dy, nullptr, nullptr, partial, out, rows, cols, p, 0);
+    return ln ? launch_column_sums<float, true>(s, dy, x, stats, partial, out, rows, cols, p, 0)
+              : launch_column_sums<float, false>(s, dy, nullptr, nullptr, partial, out, rows, cols, p, 0);
+}
+}  // namespace
+
+extern "C" int amdp_layernorm_forward(const void* x, const void* gamma, const void* beta, void* y, float* stats,
+                                      int32_t rows, int32_t cols, int32_t dtype, float eps, void* hip_stream) {
+    if (!row_op_shape_ok(rows, cols, dtype) || !(eps > 0.f)) return AMDP_E_INVAL;
+    if (rows == 0) return AMDP_OK;
+    if (!x || !gamma || !beta || !y || !stats) return AMDP_E_INVAL;
+    if (!aligned16(x) || !aligned16(gamma) || !aligned16(beta) || !aligned16(y) || ((uintptr_t)stats & 3)) return AMDP_E_INVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    return dtype == AMDP_BF16 ? launch_ln_fwd<bf16>(s, x, gamma, beta, y, stats, rows, cols, eps)
+                              : launch_ln_fwd<float>(s, x, gamma, beta, y, stats, rows, cols, eps);
+}
+
+extern "C" int amdp_layernorm_backward(const void* dy, const void* x, const float* stats, const void* gamma,
+                                       const void* res, void* dx, int32_t rows, int32_t cols, int32_t dtype,
+                                       void* hip_stream) {
+    if (!row_op_shape_ok(rows, cols, dtype)) return AMDP_E_INVAL;
+    if (rows == 0) return AMDP_OK;
+    if (!dy || !x || !stats || !gamma || !dx) return AMDP_E_INVAL;
+    if (!aligned16(dy) || !aligned16(x) || !aligned16(gamma) || !aligned16(res) || !aligned16(dx) || ((uintptr_t)stats & 3))
+        return AMDP_E_INVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    return dtype == AMDP_BF16 ? launch_ln_bwd<bf16>(s, dy, x, stats, gamma, res, dx, rows, cols)
+                              : launch_ln_bwd<float>(s, dy, x, stats, gamma, res, dx, rows, cols);
+}
+
+extern "C" size_t amdp_column_sums_workspace_bytes(int32_t rows, int32_t cols, int32_t dtype, int32_t with_layernorm) {
+    if (!row_op_shape_ok(rows, cols, dtype)) return 0;
+    // room for the most row chunks any device's plan uses
+    return (size_t)COLSUM_MAX_CHUNKS * (size_t)cols * (with_layernorm ? 2 : 1) * sizeof(float);
+}
+
+extern "C" int amdp_column_sums(const void* dy, const void* x, const float* stats, float* out, int32_t rows,
+                                int32_t cols, int32_t dtype, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
+    if (!row_op_shape_ok(rows, cols, dtype) || !out || !workspace) return AMDP_E_INVAL;
+    if (rows > 0 && (!dy || (x && !stats))) return AMDP_E_INVAL;
+    if (!aligned16(dy) || !aligned16(x) || ((uintptr_t)stats & 3) || ((uintptr_t)out & 3) || !aligned16(workspace))
+        return AMDP_E_INVAL;
+    if (workspace_bytes < amdp_column_sums_workspace_bytes(rows, cols, dtype, x != nullptr)) return AMDP_E_INVAL;
+    return column_sums_impl(dy, x, stats, out, rows, cols, dtype, (float*)workspace, COLSUM_MAX_CHUNKS,
+                            (hipStream_t)hip_stream);
 }
 
 extern "C" int amdp_device_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
