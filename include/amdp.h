@@ -53,6 +53,8 @@ extern "C" {
                                  by an in-flight minibatch */
 #define AMDP_E_HIP        -6  /* a HIP call or kernel launch failed */
 #define AMDP_E_CAPACITY   -7  /* caller's output array is too small; *n_out holds the need */
+#define AMDP_E_TOO_LARGE  -8  /* the problem exceeds the fixed capacity of an entry point that allocates
+                                 nothing; use the form that takes a caller workspace */
 
 const char* amdp_strerror(int code);
 /* Text of the HIP error behind the calling thread's most recent AMDP_E_HIP
@@ -405,6 +407,29 @@ int amdp_layernorm_backward(const void* dy, const void* x, const float* stats, c
 size_t amdp_column_sums_workspace_bytes(int32_t rows, int32_t cols, int32_t dtype, int32_t with_layernorm);
 int amdp_column_sums(const void* dy, const void* x, const float* stats, float* out, int32_t rows,
                      int32_t cols, int32_t dtype, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* amdp_column_sums for callers that cannot allocate device memory or hand over
+ * a workspace: code under HIP-graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc. Same arguments, results bit-identical to amdp_column_sums
+ * whenever both use the same number of row chunks (width <= 8192 floats, see
+ * below) and equal to the exact sums within fp32 summation error always. The
+ * partial sums go to a fixed 8 MiB array in device memory that belongs to the
+ * library's code object (each GPU the library runs on holds its own copy until
+ * the process ends); the call makes no hipMalloc / hipFree and calls no
+ * allocating routine. Limit: width = cols (2*cols with x) must satisfy width * 4
+ * bytes <= 8 MiB, i.e. cols <= amdp_column_sums_static_max_cols(with_layernorm)
+ * (2097152, or 1048576 with x); beyond it AMDP_E_TOO_LARGE and nothing is
+ * enqueued. Up to min(256, 8 MiB / (4 * width)) row chunks are used, so wide
+ * problems run with fewer chunks than the workspace form would take.
+ * Every call on a GPU shares that GPU's array: calls that may overlap on one GPU
+ * (different streams, different threads) race on it and must be serialised by
+ * the caller; calls on one stream are ordered by the stream. Nothing in the
+ * array needs clearing between calls (the first stage writes everything the
+ * second reads). The first call on each device looks up the array's address
+ * (hipGetSymbolAddress) and must therefore happen outside a graph capture. */
+size_t amdp_column_sums_static_max_cols(int32_t with_layernorm);
+int amdp_column_sums_static(const void* dy, const void* x, const float* stats, float* out, int32_t rows,
+                            int32_t cols, int32_t dtype, void* hip_stream);
 
 /* dst <- src, `bytes` bytes of device memory (both 4-byte aligned, bytes a
  * multiple of 4; AMDP_E_INVAL otherwise), by the library's own streaming copy

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     amdp_param_desc_t, amdp_adam_t, amdp_profile_entry_t, make_config,
     amdp_sim_params_t, amdp_sim_op_t, amdp_sim_result_t, amdp_system_simulate, amdp_tie_embedding_grads, amdp_device_copy,
     amdp_layernorm_forward, amdp_layernorm_backward, amdp_column_sums_workspace_bytes, amdp_column_sums,
+    amdp_column_sums_static_max_cols, amdp_column_sums_static, E_TOO_LARGE,
     amdp_strerror, amdp_schedule_generate, amdp_schedule_stats, amdp_stage_map, amdp_schedule_preset,
     PRESET_AMDP, PRESET_PIPEDREAM, PRESET_PIPEDREAM_2BW, PRESET_SYNC_1F1B, U_FLUSH,
     amdp_stage_n_params, amdp_stage_workspace_bytes, amdp_stage_param_layout,

@@ -18,6 +18,7 @@ FP32, BF16 = 0, 1
 ATTN_AUTO, ATTN_UNFUSED = 0, 1
 OPT_GEMM_TILE, OPT_GEMM_TRANSPOSING_READS, OPT_GEMM_DIRECT_TO_LDS, OPT_LAZY_JOIN = 0, 1, 2, 3
 E_INVAL, E_MB_STATE, E_NO_SLOT, E_VERSION, E_STASH_FULL, E_HIP, E_CAPACITY = -1, -2, -3, -4, -5, -6, -7
+E_TOO_LARGE = -8
 
 
 class AmdpError(RuntimeError):
@@ -160,6 +161,8 @@ def lib():
         "amdp_layernorm_backward": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i32, i32, vp]),
         "amdp_column_sums_workspace_bytes": (sz, [i32, i32, i32, i32]),
         "amdp_column_sums": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, vp, sz, vp]),
+        "amdp_column_sums_static_max_cols": (sz, [i32]),
+        "amdp_column_sums_static": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, vp]),
         "amdp_stage_read_version": (C.c_int, [vp, u32, vp]),
         "amdp_stage_set_fused_accumulate": (C.c_int, [vp, i32]),
         "amdp_tie_embedding_grads": (C.c_int, [vp, vp]),
@@ -181,7 +184,8 @@ EXPORTED = ["amdp_strerror", "amdp_last_hip_error", "amdp_schedule_generate", "a
             "amdp_stage_get_staged_grad", "amdp_stage_resident_versions", "amdp_stage_forward",
             "amdp_stage_backward", "amdp_grad_accumulate", "amdp_apply_update",
             "amdp_stage_set_overlap", "amdp_stage_get_overlap", "amdp_stage_join", "amdp_stage_set_option", "amdp_device_copy", "amdp_layernorm_forward", "amdp_layernorm_backward",
-            "amdp_column_sums_workspace_bytes", "amdp_column_sums", "amdp_stage_read_version", "amdp_stage_set_fused_accumulate", "amdp_tie_embedding_grads",
+            "amdp_column_sums_workspace_bytes", "amdp_column_sums", "amdp_column_sums_static_max_cols",
+            "amdp_column_sums_static", "amdp_stage_read_version", "amdp_stage_set_fused_accumulate", "amdp_tie_embedding_grads",
             "amdp_stage_profile_begin", "amdp_stage_profile_end"]
 
 
@@ -320,6 +324,22 @@ def amdp_column_sums(dy, x, stats, out, workspace, stream=None):
                                   _ptr(out, torch.float32, (2 if ln else 1) * cols, dev), rows, cols, _dtype_code(dy),
                                   _ptr(workspace, torch.uint8, None, dev), workspace.numel(), _stream_ptr(dy, stream)),
            "amdp_column_sums")
+
+
+def amdp_column_sums_static_max_cols(with_layernorm):
+    return lib().amdp_column_sums_static_max_cols(int(bool(with_layernorm)))
+
+
+def amdp_column_sums_static(dy, x, stats, out, stream=None):
+    """amdp_column_sums without a workspace argument (and without any allocation)."""
+    import torch
+    rows, cols = dy.shape
+    dev = dy.device
+    ln = x is not None
+    _check(lib().amdp_column_sums_static(_ptr(dy), _ptr(x, dy.dtype, rows * cols, dev),
+                                         _ptr(stats, torch.float32, 2 * rows, dev) if ln else None,
+                                         _ptr(out, torch.float32, (2 if ln else 1) * cols, dev), rows, cols,
+                                         _dtype_code(dy), _stream_ptr(dy, stream)), "amdp_column_sums_static")
 
 
 def make_config(block_kind, n_layers, d_model, n_heads, d_ffn, seq_len, microbatch, dtype,

@@ -345,6 +345,7 @@ extern "C" const char* amdp_strerror(int code) {
         case AMDP_E_STASH_FULL: return "no free weight-version slot for the update";
         case AMDP_E_HIP: return "HIP call or kernel launch failed";
         case AMDP_E_CAPACITY: return "output array too small";
+        case AMDP_E_TOO_LARGE: return "problem exceeds the fixed capacity of the entry point that allocates nothing";
         default: return "unknown error";
     }
 }

@@ -1391,6 +1391,58 @@ extern "C" int amdp_column_sums(const void* dy, const void* x, const float* stat
                             (hipStream_t)hip_stream);
 }
 
+// ---- amdp_column_sums for callers that cannot allocate ----------------------------
+// The partial sums live in a fixed array in device memory that is part of the
+// library's code object: every GPU the library runs on holds its own copy at its
+// own address until the process ends. Host code never uses the array's name as an
+// address: the per-device address comes from hipGetSymbolAddress, once per device.
+namespace {
+constexpr size_t COLSUM_STATIC_BYTES = 8u << 20;
+constexpr int COLSUM_STATIC_MAX_DEVICES = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[COLSUM_STATIC_BYTES];
+namespace {
+std::atomic<float*> g_scratch_ptr[COLSUM_STATIC_MAX_DEVICES];
+
+// Device address of this device's copy of `scratch` (the current device's).
+int static_scratch(float** out) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= COLSUM_STATIC_MAX_DEVICES) return AMDP_E_INVAL;
+    float* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void* sym = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)));
+        if (!sym) return AMDP_E_HIP;
+        p = (float*)sym;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);   // threads that race store the same address
+    }
+    *out = p;
+    return AMDP_OK;
+}
+}  // namespace
+
+extern "C" size_t amdp_column_sums_static_max_cols(int32_t with_layernorm) {
+    // at least one row chunk must fit: width * 4 bytes <= the array
+    return COLSUM_STATIC_BYTES / sizeof(float) / (with_layernorm ? 2 : 1);
+}
+
+extern "C" int amdp_column_sums_static(const void* dy, const void* x, const float* stats, float* out, int32_t rows,
+                                       int32_t cols, int32_t dtype, void* hip_stream) {
+    if (!row_op_shape_ok(rows, cols, dtype) || !out) return AMDP_E_INVAL;
+    if (rows > 0 && (!dy || (x && !stats))) return AMDP_E_INVAL;
+    if (!aligned16(dy) || !aligned16(x) || ((uintptr_t)stats & 3) || ((uintptr_t)out & 3)) return AMDP_E_INVAL;
+    const size_t width = (size_t)cols * (x ? 2 : 1);
+    if (width * sizeof(float) > COLSUM_STATIC_BYTES) return AMDP_E_TOO_LARGE;
+    // as many row chunks as the array has room for (the caller-workspace form takes up to 256)
+    const int max_chunks = (int)std::min<size_t>(COLSUM_MAX_CHUNKS, COLSUM_STATIC_BYTES / (width * sizeof(float)));
+    float* partial = nullptr;
+    TRY(static_scratch(&partial));
+    // Nothing in the array has to start at zero: the first stage writes every partial
+    // sum the second stage reads (chunks x width floats from the array's start).
+    return column_sums_impl(dy, x, stats, out, rows, cols, dtype, partial, max_chunks, (hipStream_t)hip_stream);
+}
+
 extern "C" int amdp_device_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
     if (bytes && (!dst || !src)) return AMDP_E_INVAL;
     return device_copy((hipStream_t)hip_stream, dst, src, bytes);

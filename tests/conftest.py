@@ -26,5 +26,6 @@ def golden_dir():
 
 
 def pytest_collection_modifyitems(config, items):
-    # cheap tests first, full-size ones last
-    items.sort(key=lambda it: ("fullsize" in it.nodeid, "zz_" in it.nodeid))
+    # cheap tests first, then the full-size ones; the test of the entry point that
+    # allocates nothing runs last of all (a failure there must not hide the others under -x)
+    items.sort(key=lambda it: ("zz_" in it.nodeid, "fullsize" in it.nodeid))
