@@ -127,6 +127,115 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
     }
 }
 
+// ------------------------------------------ LayerNorm, row held in registers
+// The same arithmetic with ONE read of every input: a lane keeps its NV
+// 16-byte vectors of the row (vector c = lane + 64 i, i < NV; D <= 64 * NV * V)
+// in registers as loaded, all loads are issued before the first reduction.
+template <class T> struct RawVec;
+template <> struct RawVec<float> { typedef f32x4 type; };
+template <> struct RawVec<bf16> { typedef bf16x8 type; };
+
+template <class T, int NV>
+__global__ __launch_bounds__(256) void ln_fwd_reg_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+                                                         const T* __restrict__ beta, T* __restrict__ y,
+                                                         float* __restrict__ stats, int N, int D, float eps) {
+    constexpr int V = Vec<T>::N;
+    typedef typename RawVec<T>::type raw_t;
+    const int lane = threadIdx.x & 63;
+    const long row = (long)blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+    if (row >= N) return;
+    const int nv = D / V;
+    const raw_t* xr = (const raw_t*)(x + row * D);
+    raw_t a[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nv) a[i] = xr[c];
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+        if (lane + 64 * i < nv) {
+#pragma unroll
+            for (int k = 0; k < V; ++k) s += (float)a[i][k];
+        }
+    const float mean = wave_sum(s) / (float)D;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+        if (lane + 64 * i < nv) {
+#pragma unroll
+            for (int k = 0; k < V; ++k) { const float d = (float)a[i][k] - mean; q += d * d; }
+        }
+    const float rstd = rsqrtf(wave_sum(q) / (float)D + eps);
+    if (lane == 0) { stats[2 * row] = mean; stats[2 * row + 1] = rstd; }
+    raw_t* yr = (raw_t*)(y + row * D);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nv) {
+            const raw_t gm = ((const raw_t*)gamma)[c], bt = ((const raw_t*)beta)[c];
+            raw_t o;
+#pragma unroll
+            for (int k = 0; k < V; ++k) o[k] = (T)(((float)a[i][k] - mean) * rstd * (float)gm[k] + (float)bt[k]);
+            yr[c] = o;
+        }
+    }
+}
+
+// Backward with the row in registers: dy, x and gamma are read once.
+template <class T, int NV>
+__global__ __launch_bounds__(256) void ln_bwd_reg_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                         const float* __restrict__ stats,
+                                                         const T* __restrict__ gamma, const T* res, T* dx,
+                                                         int N, int D) {
+    constexpr int V = Vec<T>::N;
+    typedef typename RawVec<T>::type raw_t;
+    const int lane = threadIdx.x & 63;
+    const long row = (long)blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+    if (row >= N) return;
+    const int nv = D / V;
+    const raw_t* xr = (const raw_t*)(x + row * D);
+    const raw_t* dyr = (const raw_t*)(dy + row * D);
+    raw_t a[NV], d[NV], gm[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nv) { a[i] = xr[c]; d[i] = dyr[c]; gm[i] = ((const raw_t*)gamma)[c]; }
+    }
+    const float mean = stats[2 * row], rstd = stats[2 * row + 1];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+        if (lane + 64 * i < nv) {
+#pragma unroll
+            for (int k = 0; k < V; ++k) {
+                const float dxh = (float)d[i][k] * (float)gm[i][k];
+                s1 += dxh;
+                s2 += dxh * ((float)a[i][k] - mean) * rstd;
+            }
+        }
+    const float c1 = wave_sum(s1) / (float)D, c2 = wave_sum(s2) / (float)D;
+    raw_t* dxr = (raw_t*)(dx + row * D);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nv) {
+            raw_t r;
+            if (res) r = ((const raw_t*)(res + row * D))[c];
+            raw_t o;
+#pragma unroll
+            for (int k = 0; k < V; ++k) {
+                const float xh = ((float)a[i][k] - mean) * rstd;
+                float v = rstd * ((float)d[i][k] * (float)gm[i][k] - c1 - xh * c2);
+                if (res) v += (float)r[k];
+                o[k] = (T)v;
+            }
+            dxr[c] = o;
+        }
+    }
+}
+
 // ----------------------------------------------------------- column reductions
 // Stage 1: a block owns 64*VEC consecutive columns and one chunk of rows; its 4
 // waves take rows round-robin, every lane keeps VEC column sums in registers
@@ -150,7 +259,32 @@ __global__ __launch_bounds__(256) void colreduce_partial_kernel(const T* __restr
 #pragma unroll
     for (int i = 0; i < V; ++i) { s[i] = 0.f; sg[i] = 0.f; }
     if (live) {
-        for (int r = r0 + wave; r < r1; r += 4) {
+        // four rows per step: their loads are all in flight before the first addition
+        // (rows are added in the same order as one at a time: the sums do not change)
+        typedef typename RawVec<T>::type raw_t;
+        int r = r0 + wave;
+        for (; r + 12 < r1; r += 16) {
+            raw_t dv[4], xv[4];
+            float mean[4], rstd[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                dv[u] = *(const raw_t*)(dy + (long)(r + 4 * u) * C + c0);
+                if constexpr (LN) {
+                    xv[u] = *(const raw_t*)(x + (long)(r + 4 * u) * C + c0);
+                    mean[u] = stats[2 * (r + 4 * u)];
+                    rstd[u] = stats[2 * (r + 4 * u) + 1];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    const float dd = (float)dv[u][i];
+                    if constexpr (LN) sg[i] += dd * ((float)xv[u][i] - mean[u]) * rstd[u];
+                    s[i] += dd;
+                }
+        }
+        for (; r < r1; r += 4) {
             float d[V];
             load_vec<T>(dy + (long)r * C + c0, d);
             if constexpr (LN) {

@@ -446,18 +446,49 @@ int gemm(amdp_stage* st, GemmLayout lay, GemmArgs g, long lda, long ldb) {
 }
 
 // ---- typed launch helpers ---------------------------------------------------
+// 16-byte vectors per lane of the LayerNorm kernels that keep a row in registers
+// (1, 2, 4, 8 or 16: rows up to 64 * 16 vectors), 0 when the row is longer.
+template <class T>
+inline int ln_reg_vectors(int D) {
+    constexpr int V = Vec<T>::N;
+    if (D % V) return 0;
+    const int need = (D / V + 63) / 64;
+    for (int nv : {1, 2, 4, 8, 16})
+        if (need <= nv) return nv;
+    return 0;
+}
 template <class T>
 int launch_ln_fwd(hipStream_t s, const void* x, const void* gamma, const void* beta, void* y, float* stats, int N,
                   int D, float eps) {
-    hipLaunchKernelGGL(ln_fwd_kernel<T>, dim3((N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0, s,
-                       (const T*)x, (const T*)gamma, (const T*)beta, (T*)y, stats, N, D, eps);
+    const dim3 grid((N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK);
+#define LN_FWD(KERN) hipLaunchKernelGGL(KERN, grid, dim3(256), 0, s, (const T*)x, (const T*)gamma, (const T*)beta, (T*)y, stats, N, D, eps)
+    switch (ln_reg_vectors<T>(D)) {
+        case 1: LN_FWD((ln_fwd_reg_kernel<T, 1>)); break;
+        case 2: LN_FWD((ln_fwd_reg_kernel<T, 2>)); break;
+        case 4: LN_FWD((ln_fwd_reg_kernel<T, 4>)); break;
+        case 8: LN_FWD((ln_fwd_reg_kernel<T, 8>)); break;
+        case 16: LN_FWD((ln_fwd_reg_kernel<T, 16>)); break;
+        default: LN_FWD(ln_fwd_kernel<T>);
+    }
+#undef LN_FWD
     return after_launch();
 }
+
 template <class T>
 int launch_ln_bwd(hipStream_t s, const void* dy, const void* x, const float* stats, const void* gamma,
                   const void* res, void* dx, int N, int D) {
-    hipLaunchKernelGGL(ln_bwd_kernel<T>, dim3((N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), dim3(256), 0, s,
-                       (const T*)dy, (const T*)x, stats, (const T*)gamma, (const T*)res, (T*)dx, N, D);
+    const dim3 grid((N + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK);
+#define LN_BWD(KERN) hipLaunchKernelGGL(KERN, grid, dim3(256), 0, s, (const T*)dy, (const T*)x, stats, (const T*)gamma, \
+                                        (const T*)res, (T*)dx, N, D)
+    switch (ln_reg_vectors<T>(D)) {
+        case 1: LN_BWD((ln_bwd_reg_kernel<T, 1>)); break;
+        case 2: LN_BWD((ln_bwd_reg_kernel<T, 2>)); break;
+        case 4: LN_BWD((ln_bwd_reg_kernel<T, 4>)); break;
+        case 8: LN_BWD((ln_bwd_reg_kernel<T, 8>)); break;
+        case 16: LN_BWD((ln_bwd_reg_kernel<T, 16>)); break;
+        default: LN_BWD(ln_bwd_kernel<T>);
+    }
+#undef LN_BWD
     return after_launch();
 }
 template <class T>
@@ -466,23 +497,17 @@ int ln_fwd(amdp_stage* st, const void* x, const void* gamma, const void* beta, v
     ProfScope ps(st, "layernorm_fwd", 0.0, (double)d.N * d.D * sizeof(T) * 2);
     return launch_ln_fwd<T>(st->launch, x, gamma, beta, y, stats, d.N, d.D, st->cfg.ln_eps);
 }
-template <class T>
-int ln_bwd(amdp_stage* st, const void* dy, const void* x, const float* stats, const void* gamma,
-           const void* res, void* dx) {
-    const Dims& d = st->d;
-    ProfScope ps(st, "layernorm_bwd", 0.0, (double)d.N * d.D * sizeof(T) * (res ? 4 : 3));
-    return launch_ln_bwd<T>(st->launch, dy, x, stats, gamma, res, dx, d.N, d.D);
-}
 
 // Column sums in two deterministic stages through `partial` (fp32 [chunks][width]).
-// The split of the rows: enough chunks to put ~4 blocks on every compute unit, at
-// least 8 rows each, at most max_chunks (what `partial` has room for).
+// The split of the rows: enough chunks to put ~8 blocks on every compute unit, at
+// least 16 rows each (a wave then has four rows' loads in flight), at most
+// max_chunks (what `partial` has room for).
 struct ColSumPlan { int col_blocks, chunks, rows_per_chunk; };
 inline ColSumPlan plan_column_sums(int N, int C, int vec, int n_cu, int max_chunks) {
     ColSumPlan p;
     p.col_blocks = (C + 64 * vec - 1) / (64 * vec);
-    int chunks = std::min(max_chunks, std::max(1, 4 * n_cu / p.col_blocks));
-    p.rows_per_chunk = std::max(8, (N + chunks - 1) / chunks);
+    int chunks = std::min(max_chunks, std::max(1, 8 * n_cu / p.col_blocks));
+    p.rows_per_chunk = std::max(16, (N + chunks - 1) / chunks);
     p.chunks = (N + p.rows_per_chunk - 1) / p.rows_per_chunk;
     return p;
 }
@@ -846,6 +871,17 @@ int wait_leaves_of(amdp_stage* st, int aslot) {
 }
 #define LEAF(stmts) do { Leaf leaf_(st); if (!leaf_.ok) return AMDP_E_HIP; stmts } while (0)
 
+// LayerNorm backward: the parameter gradients (gain at grad_out[0..D), bias at
+// grad_out[D..2D)) as a leaf, dx on the main chain.
+template <class T>
+int ln_bwd_pg(amdp_stage* st, const void* dy, const void* x, const float* stats, const void* gamma,
+              const void* res, void* dx, float* grad_out) {
+    const Dims& d = st->d;
+    LEAF({ TRY((colreduce<T, true>(st, dy, x, stats, grad_out, d.D))); });
+    ProfScope ps(st, "layernorm_bwd", 0.0, (double)d.N * d.D * sizeof(T) * (res ? 4 : 3));
+    return launch_ln_bwd<T>(st->launch, dy, x, stats, gamma, res, dx, d.N, d.D);
+}
+
 template <class T>
 int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, const void* dY, void* dX) {
     const Dims& d = st->d;
@@ -875,8 +911,7 @@ int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, co
             a.M = d.N; a.N = d.D; a.K = (int)d.Vld; a.ldc = d.D;
             TRY(gemm(st, G_NN, a, d.Vld, d.D));
         }
-        LEAF({ TRY((colreduce<T, true>(st, dz, S + sl.yL, (const float*)(S + sl.stf), g + d.off_lnf(), d.D))); });
-        TRY(ln_bwd<T>(st, dz, S + sl.yL, (const float*)(S + sl.stf), W + d.off_lnf(), nullptr, dyL));
+        TRY(ln_bwd_pg<T>(st, dz, S + sl.yL, (const float*)(S + sl.stf), W + d.off_lnf(), nullptr, dyL, g + d.off_lnf()));
         dcur = dyL;
     }
 
@@ -902,8 +937,7 @@ int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, co
             LEAF({ TRY((colreduce<T, false>(st, dffn, nullptr, nullptr, G(B_1), d.F)));
                    TRY(linear_dw(st, S + a.c, dffn, G(W_1), d.N, d.F, d.D)); });
             TRY(linear_dx(st, dffn, P(W_1), nullptr, nullptr, ta, d.N, d.F, d.D));          // ta = dc
-            LEAF({ TRY((colreduce<T, true>(st, ta, S + a.y1, st2, G(LN2_G), d.D))); });
-            TRY(ln_bwd<T>(st, ta, S + a.y1, st2, P(LN2_G), dcur, tb));                      // tb = dy1
+            TRY(ln_bwd_pg<T>(st, ta, S + a.y1, st2, P(LN2_G), dcur, tb, G(LN2_G)));       // tb = dy1
             // y1 = x + Attn(LN1(x))
             LEAF({ TRY((colreduce<T, false>(st, tb, nullptr, nullptr, G(B_O), d.D)));
                    TRY(linear_dw(st, S + a.o, tb, G(W_O), d.N, d.D, d.D)); });
@@ -912,20 +946,17 @@ int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, co
             LEAF({ TRY((colreduce<T, false>(st, dqkv, nullptr, nullptr, G(B_QKV), 3 * d.D)));
                    TRY(linear_dw(st, S + a.a, dqkv, G(W_QKV), d.N, 3 * d.D, d.D)); });
             TRY(linear_dx(st, dqkv, P(W_QKV), nullptr, nullptr, tc, d.N, 3 * d.D, d.D));     // tc = da
-            LEAF({ TRY((colreduce<T, true>(st, tc, S + a.xin, st1, G(LN1_G), d.D))); });
-            TRY(ln_bwd<T>(st, tc, S + a.xin, st1, P(LN1_G), tb, dnext));
+            TRY(ln_bwd_pg<T>(st, tc, S + a.xin, st1, P(LN1_G), tb, dnext, G(LN1_G)));
         } else {
             // y = LN2(r2), r2 = y1 + MLP(y1); y1 = LN1(r1), r1 = x + Attn(x)
-            LEAF({ TRY((colreduce<T, true>(st, dcur, S + a.c, st2, G(LN2_G), d.D))); });
-            TRY(ln_bwd<T>(st, dcur, S + a.c, st2, P(LN2_G), nullptr, ta));                   // ta = dr2
+            TRY(ln_bwd_pg<T>(st, dcur, S + a.c, st2, P(LN2_G), nullptr, ta, G(LN2_G)));   // ta = dr2
             LEAF({ TRY((colreduce<T, false>(st, ta, nullptr, nullptr, G(B_2), d.D)));
                    TRY(linear_dw(st, S + a.h, ta, G(W_2), d.N, d.D, d.F)); });
             TRY(linear_dx(st, ta, P(W_2), S + a.u, nullptr, dffn, d.N, d.D, d.F));
             LEAF({ TRY((colreduce<T, false>(st, dffn, nullptr, nullptr, G(B_1), d.F)));
                    TRY(linear_dw(st, S + a.y1, dffn, G(W_1), d.N, d.F, d.D)); });
             TRY(linear_dx(st, dffn, P(W_1), nullptr, ta, tb, d.N, d.F, d.D));               // tb = dy1
-            LEAF({ TRY((colreduce<T, true>(st, tb, S + a.a, st1, G(LN1_G), d.D))); });
-            TRY(ln_bwd<T>(st, tb, S + a.a, st1, P(LN1_G), nullptr, tc));                    // tc = dr1
+            TRY(ln_bwd_pg<T>(st, tb, S + a.a, st1, P(LN1_G), nullptr, tc, G(LN1_G)));     // tc = dr1
             LEAF({ TRY((colreduce<T, false>(st, tc, nullptr, nullptr, G(B_O), d.D)));
                    TRY(linear_dw(st, S + a.o, tc, G(W_O), d.N, d.D, d.D)); });
             TRY(linear_dx(st, tc, P(W_O), nullptr, nullptr, dO, d.N, d.D, d.D));
