@@ -450,9 +450,13 @@ int amdp_device_copy(void* dst, const void* src, size_t bytes, void* hip_stream)
  *   AMDP_OPT_GEMM_DIRECT_TO_LDS      tiles loaded from global memory straight into LDS: 1 (default)
  *                                    where measured faster, 0 never, 2 wherever the shape allows
  *   AMDP_OPT_LAZY_JOIN               1 (default) a backward leaves its gradient leaves running on the
- *                                    side stream; 0 it ends by joining them */
+ *                                    side stream; 0 it ends by joining them
+ *   AMDP_OPT_SPLIT_K_MIN_TOKENS      a weight-gradient product too small to give every compute unit a
+ *                                    128x128 tile is split over its tokens into up to eight parts that
+ *                                    are added in fixed order; a part contracts at least this many
+ *                                    tokens (default 512, at least 64; a large value switches it off) */
 enum { AMDP_OPT_GEMM_TILE = 0, AMDP_OPT_GEMM_TRANSPOSING_READS = 1, AMDP_OPT_GEMM_DIRECT_TO_LDS = 2,
-       AMDP_OPT_LAZY_JOIN = 3 };
+       AMDP_OPT_LAZY_JOIN = 3, AMDP_OPT_SPLIT_K_MIN_TOKENS = 4 };
 int amdp_stage_set_option(amdp_stage_t* stage, int32_t option, int32_t value);
 
 /* The input embedding of the first stage and the output projection of the last

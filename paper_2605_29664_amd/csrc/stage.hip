@@ -123,6 +123,7 @@ struct Carve {
     std::vector<BwdScratch> bw;
     size_t lm_dz, lm_dy, dO, dP, partial, row_loss, total;
     size_t pk_qkv = 0, pk_dqkv = 0, pk_o = 0, pk_do = 0;   // head-padded copies for the fused attention
+    size_t splitk = 0, splitk_bytes = 0;                   // parts of a weight-gradient product split over its tokens
     int partial_chunks;
     SlotLayout slot;
 };
@@ -186,6 +187,11 @@ void carve(const Dims& d, const amdp_stage_config_t& c, Carve* w) {
         const size_t NDp = pk ? (size_t)d.N * d.H * flash_head_dim(d) * d.esz : 0;
         w->pk_qkv = take(3 * NDp); w->pk_dqkv = take(3 * NDp); w->pk_o = take(NDp); w->pk_do = take(NDp);
     }
+    // Only the D x D product of a narrow layer is ever split (the others have three to
+    // sixteen times as many tiles); room for eight parts while its 128x128 tiles would
+    // leave half of a 256-unit GPU idle.
+    w->splitk_bytes = (d.bf && d.D % 128 == 0 && (long)(d.D / 128) * (d.D / 128) * 2 <= 256) ? (size_t)8 * d.D * d.D * 4 : 0;
+    w->splitk = take(w->splitk_bytes);
     w->partial_chunks = 256;
     const size_t maxw = (size_t)std::max(std::max(3 * d.D, d.F), 2 * d.D);
     w->partial = take((size_t)w->partial_chunks * maxw * 4);
@@ -252,6 +258,7 @@ struct amdp_stage {
     uint64_t free_counter = 0;
     bool overlap = true;
     bool fused_acc = false;        // backward adds parameter gradients into G directly
+    int splitk_min_k = 512;        // fewest tokens a part of a split weight-gradient product contracts
     bool flash = true;      // fused attention kernels (shape permitting); false: scores, softmax, probabilities in HBM
     hipEvent_t next_event() { ev_next = (ev_next + 1) % 16; return events[ev_next]; }
 
@@ -755,13 +762,52 @@ int linear_dx(amdp_stage* st, const void* dY, const void* W, const void* gelu_u,
     g.epi.gelu_u = gelu_u; g.epi.ldu = K; g.epi.res = res; g.epi.ldr = K;
     return gemm(st, G_NT, g, N, N);
 }
+// How many ways the token dimension of a weight-gradient product [rows x cols] is
+// split over workgroups (1 = not at all). A product whose 128x128 tiles cover at
+// most half of the compute units gets one workgroup per unit instead: the parts
+// go to scratch and are added in fixed order afterwards (no float atomics).
+int dw_split(const amdp_stage* st, int rows, int cols, int tokens) {
+    if (!st->d.bf || st->force_tile != 0 || rows % 128 || cols % 128 || !st->w.splitk_bytes) return 1;
+    const long tiles = (long)(rows / 128) * (cols / 128);
+    int ways = 1;
+    while (ways < 8 && tiles * ways * 2 <= st->n_cu && tokens % (ways * 2 * MF_BK) == 0 &&
+           tokens / (ways * 2) >= st->splitk_min_k &&
+           (size_t)rows * cols * 4 * (size_t)(ways * 2) <= st->w.splitk_bytes)
+        ways *= 2;
+    return ways;
+}
 // dW[K,N] (fp32) = X[M,K]^T dY[M,N]
 int linear_dw(amdp_stage* st, const void* X, const void* dY, float* dW, int M, int N, int K) {
     GemmArgs g{};
     g.A = X; g.B = dY; g.C = dW; g.M = K; g.N = N; g.K = M; g.ldc = N;
     g.epi.out_f32 = 1;
     g.epi.accumulate = st->fused_acc ? 1 : 0;
-    return gemm(st, G_TN, g, K, N);
+    const int ways = dw_split(st, K, N, M);
+    if (ways == 1) return gemm(st, G_TN, g, K, N);
+    // one batched launch: part z contracts tokens [z * M/ways, (z+1) * M/ways) into partial[z]
+    float* partial = st->at<float>(st->w.splitk);
+    const int Mz = M / ways;
+    g.C = partial; g.K = Mz; g.epi.accumulate = 0;
+    g.batch = ways; g.batch_inner = 1;
+    g.a_rs = 1; g.a_cs = K; g.b_rs = N; g.b_cs = 1;
+    g.a_bo = (long)Mz * K; g.b_bo = (long)Mz * N; g.c_bo = (long)K * N;
+    if (!mfma_shape_ok<128, 128>(g, true, true)) {      // alignment the tile kernel needs: fall back to one launch
+        GemmArgs one{};
+        one.A = X; one.B = dY; one.C = dW; one.M = K; one.N = N; one.K = M; one.ldc = N;
+        one.epi.out_f32 = 1; one.epi.accumulate = st->fused_acc ? 1 : 0;
+        return gemm(st, G_TN, one, K, N);
+    }
+    {
+        ProfScope ps(st, "gemm_mfma128x128_TN_splitk", 2.0 * K * (double)N * M, 0.0);
+        hipError_t e = st->use_tr ? launch_gemm_mfma_inst<128, 128, true, true, true, 4>(g, st->launch)
+                                  : launch_gemm_mfma_inst<128, 128, true, true, false, 4>(g, st->launch);
+        if (!hip_ok(e, "gemm_mfma128x128_TN_splitk")) return AMDP_E_HIP;
+    }
+    const long n4 = (long)K * N / 4;
+    ProfScope ps(st, "splitk_reduce", 0.0, (double)K * N * 4 * (ways + 1 + (st->fused_acc ? 1 : 0)));
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(direct_grid(n4, ACC_BLOCK)), dim3(ACC_BLOCK), 0, st->launch, dW,
+                       partial, n4, ways, st->fused_acc ? 1 : 0);
+    return after_launch();
 }
 
 template <class T>
@@ -1495,6 +1541,10 @@ extern "C" int amdp_stage_set_option(amdp_stage_t* st, int32_t option, int32_t v
         case AMDP_OPT_LAZY_JOIN:
             TRY(join_leaves(st));
             st->lazy_join = value != 0;
+            return AMDP_OK;
+        case AMDP_OPT_SPLIT_K_MIN_TOKENS:
+            if (value < 64) return AMDP_E_INVAL;
+            st->splitk_min_k = value;
             return AMDP_OK;
     }
     return AMDP_E_INVAL;

@@ -123,6 +123,21 @@ __global__ __launch_bounds__(ACC_BLOCK) void zero16_kernel(u32x4* __restrict__ d
     dst[i] = z;
 }
 
+// out (+)= partial[0] + partial[1] + ... + partial[parts-1], each of n4 float4, added in that order:
+// the second stage of a product whose contraction was split over workgroups.
+__global__ __launch_bounds__(ACC_BLOCK) void splitk_reduce_kernel(float* __restrict__ out,
+                                                                  const float* __restrict__ partial, long n4,
+                                                                  int parts, int accumulate) {
+    const long i = (long)blockIdx.x * ACC_BLOCK + threadIdx.x;
+    if (i >= n4) return;
+    const f32x4* p4 = (const f32x4*)partial;
+    f32x4 s = p4[i];
+    for (int k = 1; k < parts; ++k) s += p4[(long)k * n4 + i];
+    f32x4* o4 = (f32x4*)out;
+    if (accumulate) s += o4[i];
+    o4[i] = s;
+}
+
 // grid for the grid-stride helpers (copy, zero, publish)
 inline int stream_grid(long n4) {
     long blocks = (n4 + STREAM_BLOCK - 1) / STREAM_BLOCK;

@@ -9,7 +9,7 @@ import workloads as W
 from oracle import schedule as OSched
 from tests.parity import run_parity, worst_entries, GpuStage, rel_err, TOL
 from paper_2605_29664_amd.binding import (OPT_GEMM_TILE, OPT_GEMM_TRANSPOSING_READS, OPT_GEMM_DIRECT_TO_LDS,
-                                          OPT_LAZY_JOIN, ATTN_UNFUSED)
+                                          OPT_LAZY_JOIN, OPT_SPLIT_K_MIN_TOKENS, ATTN_UNFUSED)
 
 pytestmark = pytest.mark.gpu
 
@@ -104,6 +104,40 @@ def test_tile_bf16_ragged_last_tile(key, tile):
     rep = run_parity(W.TINY[key], n_windows=1, verbose=False, options={OPT_GEMM_TILE: tile})
     _report(f"{key}_ragged_{tile}", rep)
     assert rep["ok"], worst_entries(rep)
+
+
+@pytest.mark.parametrize("key", ["gpt_tile", "bert_tile"])
+def test_weight_gradients_split_over_tokens(key):
+    """Weight-gradient products too small to fill the GPU are split over their
+    tokens into parts that are added in fixed order. At the tile test shapes
+    that needs the part size lowered to 64 tokens (default 512): the 256x256
+    product then runs in four parts, the wider ones in two. Checked against the
+    oracle, run to run, and with the accumulation fused into the second stage."""
+    import torch
+    w = W.TINY[key]
+    rep = run_parity(w, n_windows=1, verbose=False, options={OPT_SPLIT_K_MIN_TOKENS: 64})
+    _report(f"{key}_split_k", rep)
+    assert rep["ok"], worst_entries(rep)
+    from oracle.stage import Stage as OStage
+    theta0 = W.make_theta(w, OStage.from_workload(w).layout)
+    aux = W.make_aux(w, 0)
+    sums = []
+    for fused, split in ((False, 64), (False, 64), (True, 64), (False, 1 << 20)):
+        gpu = GpuStage(w, act_slots=2, stash_slots=1, options={OPT_SPLIT_K_MIN_TOKENS: split})
+        gpu.set_state(theta0)
+        gpu.stage.amdp_stage_set_fused_accumulate(fused)
+        x, dy = gpu.to_dev(W.make_x(w, 0), gpu.dt), gpu.to_dev(W.make_dy(w, 0), gpu.dt)
+        a = None if aux is None else gpu.to_dev(np.asarray(aux, dtype=np.int32))
+        y = torch.empty_like(x)
+        for mb in (0, 1):
+            gpu.stage.amdp_stage_forward(mb, 0, x, a, y)
+            gpu.stage.amdp_stage_backward(mb, 0, dy, None)
+            gpu.stage.amdp_grad_accumulate(mb)
+        sums.append(gpu.state(("G",))["G"])
+        gpu.stage.close()
+    assert np.array_equal(sums[0], sums[1]) and np.array_equal(sums[0], sums[2])
+    assert not np.array_equal(sums[0], sums[3]), "the split path did not run"      # another summation order
+    assert rel_err(sums[0], sums[3]) < 1e-5
 
 
 @pytest.mark.parametrize("key", ["gpt_tile64", "bert_dh50", "bert_tile_dh50", "gpt_tile_dh96"])
