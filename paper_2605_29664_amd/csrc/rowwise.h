@@ -317,6 +317,133 @@ __global__ __launch_bounds__(256) void colreduce_partial_kernel(const T* __restr
         }
     }
 }
+// ---- several column reductions in one pair of launches ----------------------
+// All bias and LayerNorm-parameter gradients of one layer's backward: up to 8
+// segments, each a [N, C] matrix dy (LayerNorm segments also x and the row
+// statistics) with its own output vector. The partial sums of all segments sit
+// side by side in one row of `partial` per row chunk (segment i at column
+// woff, width C or 2 C).
+struct ColSumSeg {
+    const void* dy;
+    const void* x;          // null: plain column sums; else LayerNorm input
+    const float* stats;
+    float* out;
+    int C, first_block, woff, width;
+};
+struct ColSumBatch {
+    ColSumSeg seg[8];
+    int n, N, rows_per_chunk, width;
+};
+
+template <class T>
+__global__ __launch_bounds__(256) void colsum_batch_partial_kernel(ColSumBatch b, float* __restrict__ partial) {
+    constexpr int V = Vec<T>::N;
+    typedef typename RawVec<T>::type raw_t;
+    __shared__ float red[2][4][64 * V];
+    int si = 0;
+    for (int i = 1; i < b.n; ++i)
+        if ((int)blockIdx.x >= b.seg[i].first_block) si = i;
+    const T* dy = (const T*)b.seg[si].dy;
+    const T* x = (const T*)b.seg[si].x;
+    const float* stats = b.seg[si].stats;
+    const int C = b.seg[si].C, woff = b.seg[si].woff;
+    const bool ln = x != nullptr;                   // uniform over the block
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cb = blockIdx.x - b.seg[si].first_block;
+    const int c0 = (cb * 64 + lane) * V;
+    const bool live = c0 < C;
+    const int r0 = blockIdx.y * b.rows_per_chunk, r1 = min(b.N, r0 + b.rows_per_chunk);
+    float s[V], sg[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) { s[i] = 0.f; sg[i] = 0.f; }
+    if (live) {
+        int r = r0 + wave;
+        for (; r + 12 < r1; r += 16) {              // four rows' loads in flight before the first addition
+            raw_t dv[4], xv[4];
+            float mean[4], rstd[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                dv[u] = *(const raw_t*)(dy + (long)(r + 4 * u) * C + c0);
+                if (ln) {
+                    xv[u] = *(const raw_t*)(x + (long)(r + 4 * u) * C + c0);
+                    mean[u] = stats[2 * (r + 4 * u)];
+                    rstd[u] = stats[2 * (r + 4 * u) + 1];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    const float dd = (float)dv[u][i];
+                    if (ln) sg[i] += dd * ((float)xv[u][i] - mean[u]) * rstd[u];
+                    s[i] += dd;
+                }
+        }
+        for (; r < r1; r += 4) {
+            const raw_t dv = *(const raw_t*)(dy + (long)r * C + c0);
+            if (ln) {
+                const raw_t xv = *(const raw_t*)(x + (long)r * C + c0);
+                const float mean = stats[2 * r], rstd = stats[2 * r + 1];
+#pragma unroll
+                for (int i = 0; i < V; ++i) sg[i] += (float)dv[i] * ((float)xv[i] - mean) * rstd;
+            }
+#pragma unroll
+            for (int i = 0; i < V; ++i) s[i] += (float)dv[i];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        red[0][wave][lane * V + i] = s[i];
+        red[1][wave][lane * V + i] = sg[i];
+    }
+    __syncthreads();
+    float* prow = partial + (long)blockIdx.y * b.width + woff;
+    for (int j = threadIdx.x; j < 64 * V; j += 256) {
+        const int c = cb * 64 * V + j;
+        if (c >= C) continue;
+        const float t = red[0][0][j] + red[0][1][j] + red[0][2][j] + red[0][3][j];
+        if (ln) {
+            prow[c] = red[1][0][j] + red[1][1][j] + red[1][2][j] + red[1][3][j];
+            prow[C + c] = t;
+        } else {
+            prow[c] = t;
+        }
+    }
+}
+
+// Second stage over the concatenated width: column j belongs to the segment whose
+// [woff, woff + width) holds it and goes to that segment's output vector.
+__global__ __launch_bounds__(256) void colsum_batch_final_kernel(ColSumBatch b, const float* __restrict__ partial,
+                                                                 int chunks, int accumulate) {
+    __shared__ float red[16][17];
+    const int j = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int c = blockIdx.x * 16 + j;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (c < b.width) {
+        const float* p = partial + c;
+        int k = grp;
+        for (; k + 48 < chunks; k += 64) {
+            s0 += p[(long)k * b.width];
+            s1 += p[(long)(k + 16) * b.width];
+            s2 += p[(long)(k + 32) * b.width];
+            s3 += p[(long)(k + 48) * b.width];
+        }
+        for (; k < chunks; k += 16) s0 += p[(long)k * b.width];
+    }
+    red[grp][j] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (grp == 0 && c < b.width) {
+        float t = 0.f;
+#pragma unroll
+        for (int g = 0; g < 16; ++g) t += red[g][j];
+        int si = 0;
+        for (int i = 1; i < b.n; ++i)
+            if (c >= b.seg[i].woff) si = i;
+        float* o = b.seg[si].out + (c - b.seg[si].woff);
+        *o = accumulate ? *o + t : t;
+    }
+}
+
 // Stage 2: out[c] = sum over chunks. A block owns 16 columns; its 16 groups of
 // 16 threads each sum every 16th chunk (four loads in flight per thread: the
 // sums are short, so the kernel lives on memory latency), then the groups are

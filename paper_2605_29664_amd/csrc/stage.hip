@@ -193,7 +193,8 @@ void carve(const Dims& d, const amdp_stage_config_t& c, Carve* w) {
     w->splitk_bytes = (d.bf && d.D % 128 == 0 && (long)(d.D / 128) * (d.D / 128) * 2 <= 256) ? (size_t)8 * d.D * d.D * 4 : 0;
     w->splitk = take(w->splitk_bytes);
     w->partial_chunks = 256;
-    const size_t maxw = (size_t)std::max(std::max(3 * d.D, d.F), 2 * d.D);
+    // one row of partial sums per row chunk for all six column reductions of a layer's backward
+    const size_t maxw = (size_t)9 * d.D + d.F;
     w->partial = take((size_t)w->partial_chunks * maxw * 4);
     w->row_loss = take((size_t)d.N * 4);
     w->total = off;
@@ -532,13 +533,39 @@ int launch_column_sums(hipStream_t s, const void* dy, const void* x, const float
                        p.chunks, accumulate);
     return after_launch();
 }
-template <class T, bool LN>
-int colreduce(amdp_stage* st, const void* dy, const void* x, const float* stats, float* out, int C) {
-    const Dims& d = st->d;
-    const ColSumPlan p = plan_column_sums(d.N, C, Vec<T>::N, st->n_cu, st->w.partial_chunks);
-    ProfScope ps(st, LN ? "colreduce_ln" : "colreduce_bias", 0.0, (double)d.N * C * sizeof(T) * (LN ? 2 : 1));
-    return launch_column_sums<T, LN>(st->launch, dy, x, stats, st->at<float>(st->w.partial), out, d.N, C, p,
-                                     st->fused_acc ? 1 : 0);
+// The bias and LayerNorm-parameter gradients of one layer's backward, collected while the
+// chain runs and reduced together in one pair of launches at the end of the layer (their
+// inputs live in the layer's own scratch and in the activation slot until then).
+struct ColSumList {
+    ColSumBatch b;
+    int blocks = 0;
+    double bytes = 0.0;
+    explicit ColSumList(int N) { b.n = 0; b.N = N; b.width = 0; b.rows_per_chunk = 0; }
+};
+// out[0..C) = column sums of dy [N, C]; with x: out[0..C) = sum dy*xhat, out[C..2C) = sum dy
+template <class T>
+void colsum_add(ColSumList& L, const void* dy, const void* x, const float* stats, float* out, int C) {
+    ColSumSeg& sg = L.b.seg[L.b.n++];
+    sg.dy = dy; sg.x = x; sg.stats = stats; sg.out = out; sg.C = C;
+    sg.first_block = L.blocks; sg.woff = L.b.width; sg.width = x ? 2 * C : C;
+    L.blocks += (C + 64 * Vec<T>::N - 1) / (64 * Vec<T>::N);
+    L.b.width += sg.width;
+    L.bytes += (double)L.b.N * C * sizeof(T) * (x ? 2 : 1);
+}
+template <class T>
+int colsum_flush(amdp_stage* st, ColSumList& L) {
+    if (L.b.n == 0) return AMDP_OK;
+    // ~8 blocks per compute unit, at least 16 rows per chunk (four rows' loads in flight per wave)
+    int chunks = std::min(st->w.partial_chunks, std::max(1, 8 * st->n_cu / L.blocks));
+    L.b.rows_per_chunk = std::max(16, (L.b.N + chunks - 1) / chunks);
+    chunks = (L.b.N + L.b.rows_per_chunk - 1) / L.b.rows_per_chunk;
+    float* partial = st->at<float>(st->w.partial);
+    ProfScope ps(st, "column_sums", 0.0, L.bytes);
+    hipLaunchKernelGGL(colsum_batch_partial_kernel<T>, dim3(L.blocks, chunks), dim3(256), 0, st->launch, L.b, partial);
+    TRY(after_launch());
+    hipLaunchKernelGGL(colsum_batch_final_kernel, dim3((L.b.width + 15) / 16), dim3(256), 0, st->launch, L.b, partial,
+                       chunks, st->fused_acc ? 1 : 0);
+    return after_launch();
 }
 
 GemmArgs attn_batch(const Dims& d) {
@@ -917,13 +944,13 @@ int wait_leaves_of(amdp_stage* st, int aslot) {
 }
 #define LEAF(stmts) do { Leaf leaf_(st); if (!leaf_.ok) return AMDP_E_HIP; stmts } while (0)
 
-// LayerNorm backward: the parameter gradients (gain at grad_out[0..D), bias at
-// grad_out[D..2D)) as a leaf, dx on the main chain.
+// LayerNorm backward: dx on the main chain; the parameter gradients (gain at
+// grad_out[0..D), bias at grad_out[D..2D)) join the layer's column reductions.
 template <class T>
-int ln_bwd_pg(amdp_stage* st, const void* dy, const void* x, const float* stats, const void* gamma,
+int ln_bwd_pg(amdp_stage* st, ColSumList& cs, const void* dy, const void* x, const float* stats, const void* gamma,
               const void* res, void* dx, float* grad_out) {
     const Dims& d = st->d;
-    LEAF({ TRY((colreduce<T, true>(st, dy, x, stats, grad_out, d.D))); });
+    colsum_add<T>(cs, dy, x, stats, grad_out, d.D);
     ProfScope ps(st, "layernorm_bwd", 0.0, (double)d.N * d.D * sizeof(T) * (res ? 4 : 3));
     return launch_ln_bwd<T>(st->launch, dy, x, stats, gamma, res, dx, d.N, d.D);
 }
@@ -957,7 +984,9 @@ int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, co
             a.M = d.N; a.N = d.D; a.K = (int)d.Vld; a.ldc = d.D;
             TRY(gemm(st, G_NN, a, d.Vld, d.D));
         }
-        TRY(ln_bwd_pg<T>(st, dz, S + sl.yL, (const float*)(S + sl.stf), W + d.off_lnf(), nullptr, dyL, g + d.off_lnf()));
+        ColSumList cs(d.N);
+        TRY(ln_bwd_pg<T>(st, cs, dz, S + sl.yL, (const float*)(S + sl.stf), W + d.off_lnf(), nullptr, dyL, g + d.off_lnf()));
+        LEAF({ TRY(colsum_flush<T>(st, cs)); });
         dcur = dyL;
     }
 
@@ -974,43 +1003,45 @@ int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, co
         void* dnext = (l == 0 && dX) ? dX : st->at<>(bw.dxout);
         const float* st1 = (const float*)(S + a.st1);
         const float* st2 = (const float*)(S + a.st2);
+        ColSumList cs(d.N);
 
         if (d.causal) {
             // y = y1 + MLP(LN2(y1))
-            LEAF({ TRY((colreduce<T, false>(st, dcur, nullptr, nullptr, G(B_2), d.D)));
-                   TRY(linear_dw(st, S + a.h, dcur, G(W_2), d.N, d.D, d.F)); });
+            colsum_add<T>(cs, dcur, nullptr, nullptr, G(B_2), d.D);
+            LEAF({ TRY(linear_dw(st, S + a.h, dcur, G(W_2), d.N, d.D, d.F)); });
             TRY(linear_dx(st, dcur, P(W_2), S + a.u, nullptr, dffn, d.N, d.D, d.F));
-            LEAF({ TRY((colreduce<T, false>(st, dffn, nullptr, nullptr, G(B_1), d.F)));
-                   TRY(linear_dw(st, S + a.c, dffn, G(W_1), d.N, d.F, d.D)); });
+            colsum_add<T>(cs, dffn, nullptr, nullptr, G(B_1), d.F);
+            LEAF({ TRY(linear_dw(st, S + a.c, dffn, G(W_1), d.N, d.F, d.D)); });
             TRY(linear_dx(st, dffn, P(W_1), nullptr, nullptr, ta, d.N, d.F, d.D));          // ta = dc
-            TRY(ln_bwd_pg<T>(st, ta, S + a.y1, st2, P(LN2_G), dcur, tb, G(LN2_G)));       // tb = dy1
+            TRY(ln_bwd_pg<T>(st, cs, ta, S + a.y1, st2, P(LN2_G), dcur, tb, G(LN2_G)));   // tb = dy1
             // y1 = x + Attn(LN1(x))
-            LEAF({ TRY((colreduce<T, false>(st, tb, nullptr, nullptr, G(B_O), d.D)));
-                   TRY(linear_dw(st, S + a.o, tb, G(W_O), d.N, d.D, d.D)); });
+            colsum_add<T>(cs, tb, nullptr, nullptr, G(B_O), d.D);
+            LEAF({ TRY(linear_dw(st, S + a.o, tb, G(W_O), d.N, d.D, d.D)); });
             TRY(linear_dx(st, tb, P(W_O), nullptr, nullptr, dO, d.N, d.D, d.D));
             TRY(attention_bwd<T>(st, dO, S + a.qkv, S + a.P, S + a.o, dP, dqkv, valid));
-            LEAF({ TRY((colreduce<T, false>(st, dqkv, nullptr, nullptr, G(B_QKV), 3 * d.D)));
-                   TRY(linear_dw(st, S + a.a, dqkv, G(W_QKV), d.N, 3 * d.D, d.D)); });
+            colsum_add<T>(cs, dqkv, nullptr, nullptr, G(B_QKV), 3 * d.D);
+            LEAF({ TRY(linear_dw(st, S + a.a, dqkv, G(W_QKV), d.N, 3 * d.D, d.D)); });
             TRY(linear_dx(st, dqkv, P(W_QKV), nullptr, nullptr, tc, d.N, 3 * d.D, d.D));     // tc = da
-            TRY(ln_bwd_pg<T>(st, tc, S + a.xin, st1, P(LN1_G), tb, dnext, G(LN1_G)));
+            TRY(ln_bwd_pg<T>(st, cs, tc, S + a.xin, st1, P(LN1_G), tb, dnext, G(LN1_G)));
         } else {
             // y = LN2(r2), r2 = y1 + MLP(y1); y1 = LN1(r1), r1 = x + Attn(x)
-            TRY(ln_bwd_pg<T>(st, dcur, S + a.c, st2, P(LN2_G), nullptr, ta, G(LN2_G)));   // ta = dr2
-            LEAF({ TRY((colreduce<T, false>(st, ta, nullptr, nullptr, G(B_2), d.D)));
-                   TRY(linear_dw(st, S + a.h, ta, G(W_2), d.N, d.D, d.F)); });
+            TRY(ln_bwd_pg<T>(st, cs, dcur, S + a.c, st2, P(LN2_G), nullptr, ta, G(LN2_G)));   // ta = dr2
+            colsum_add<T>(cs, ta, nullptr, nullptr, G(B_2), d.D);
+            LEAF({ TRY(linear_dw(st, S + a.h, ta, G(W_2), d.N, d.D, d.F)); });
             TRY(linear_dx(st, ta, P(W_2), S + a.u, nullptr, dffn, d.N, d.D, d.F));
-            LEAF({ TRY((colreduce<T, false>(st, dffn, nullptr, nullptr, G(B_1), d.F)));
-                   TRY(linear_dw(st, S + a.y1, dffn, G(W_1), d.N, d.F, d.D)); });
+            colsum_add<T>(cs, dffn, nullptr, nullptr, G(B_1), d.F);
+            LEAF({ TRY(linear_dw(st, S + a.y1, dffn, G(W_1), d.N, d.F, d.D)); });
             TRY(linear_dx(st, dffn, P(W_1), nullptr, ta, tb, d.N, d.F, d.D));               // tb = dy1
-            TRY(ln_bwd_pg<T>(st, tb, S + a.a, st1, P(LN1_G), nullptr, tc, G(LN1_G)));     // tc = dr1
-            LEAF({ TRY((colreduce<T, false>(st, tc, nullptr, nullptr, G(B_O), d.D)));
-                   TRY(linear_dw(st, S + a.o, tc, G(W_O), d.N, d.D, d.D)); });
+            TRY(ln_bwd_pg<T>(st, cs, tb, S + a.a, st1, P(LN1_G), nullptr, tc, G(LN1_G)));     // tc = dr1
+            colsum_add<T>(cs, tc, nullptr, nullptr, G(B_O), d.D);
+            LEAF({ TRY(linear_dw(st, S + a.o, tc, G(W_O), d.N, d.D, d.D)); });
             TRY(linear_dx(st, tc, P(W_O), nullptr, nullptr, dO, d.N, d.D, d.D));
             TRY(attention_bwd<T>(st, dO, S + a.qkv, S + a.P, S + a.o, dP, dqkv, valid));
-            LEAF({ TRY((colreduce<T, false>(st, dqkv, nullptr, nullptr, G(B_QKV), 3 * d.D)));
-                   TRY(linear_dw(st, S + a.xin, dqkv, G(W_QKV), d.N, 3 * d.D, d.D)); });
+            colsum_add<T>(cs, dqkv, nullptr, nullptr, G(B_QKV), 3 * d.D);
+            LEAF({ TRY(linear_dw(st, S + a.xin, dqkv, G(W_QKV), d.N, 3 * d.D, d.D)); });
             TRY(linear_dx(st, dqkv, P(W_QKV), nullptr, tc, dnext, d.N, 3 * d.D, d.D));
         }
+        LEAF({ TRY(colsum_flush<T>(st, cs)); });
         // the leaves of this layer read the caller's dY: remember where they end
         if (dcur == dY && dY && st->overlap) {
             HIP_TRY(hipEventRecord(st->input_ev, st->side));
