@@ -270,6 +270,12 @@ def main():
         for nm, row in result["streaming"].items():
             row["frac_of_copy_ceiling"] = row["gbs"] / copy_gbs
 
+    # ---- the row kernels on their own (entry points amdp_layernorm_* / amdp_column_sums) at the
+    # stage's own size, where a launch moves a few tens of MB and is bound by launch and memory
+    # latency, and at 16 times the rows, where it is bound by HBM ------------------------------
+    if not args.no_profile and w.dtype == 1:
+        result["row_kernels"] = row_kernel_rates(torch, amdp, w, dev)
+
     # padded sequences (bidirectional blocks): tokens that are not padding, per second
     if w.block_kind != 0 and not w.has_lm_head:
         valid = 0
@@ -303,6 +309,46 @@ def main():
         result["cpu_baseline"] = cpu_baseline(w)
 
     print(json.dumps(result))
+
+
+def row_kernel_rates(torch, amdp, w, dev):
+    """GB/s of algorithmic traffic (each input read once, each output written once) of the
+    LayerNorm and column-sum kernels through their own entry points, HIP-event timed."""
+    out = {}
+    D = w.d_model
+    for label, rows in (("stage_rows", w.tokens), ("rows_x16", 16 * w.tokens)):
+        x = torch.randn((rows, D), device=dev, dtype=torch.float32).to(torch.bfloat16)
+        dy = (1e-3 * torch.randn((rows, D), device=dev, dtype=torch.float32)).to(torch.bfloat16)
+        res = dy.clone()
+        g = torch.ones(D, device=dev, dtype=torch.bfloat16)
+        y, dx = torch.empty_like(x), torch.empty_like(x)
+        stats = torch.empty((rows, 2), device=dev, dtype=torch.float32)
+        ws = torch.empty(amdp.amdp_column_sums_workspace_bytes(rows, D, amdp.BF16, True), dtype=torch.uint8, device=dev)
+        sums = torch.empty(2 * D, device=dev, dtype=torch.float32)
+        nb = rows * D * 2
+        cases = {
+            "layernorm_fwd": (lambda: amdp.amdp_layernorm_forward(x, g, g, y, stats, 1e-5), 2 * nb),
+            "layernorm_bwd": (lambda: amdp.amdp_layernorm_backward(dy, x, stats, g, res, dx), 4 * nb),
+            "column_sums_bias": (lambda: amdp.amdp_column_sums(dy, None, None, sums, ws), nb),
+            "column_sums_layernorm": (lambda: amdp.amdp_column_sums(dy, x, stats, sums, ws), 2 * nb),
+        }
+        row = {}
+        for name, (fn, nbytes) in cases.items():
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            n_it = 20
+            e0.record()
+            for _ in range(n_it):
+                fn()
+            e1.record()
+            e1.synchronize()
+            ms = e0.elapsed_time(e1) / n_it
+            row[name] = {"us": round(1e3 * ms, 2), "gbs": round(nbytes / ms / 1e6, 1),
+                         "frac_of_hbm_peak": round(nbytes / ms / 1e6 / PEAK_HBM_GBS, 3)}
+        out[label] = {"rows": rows, "cols": D, **row}
+        del x, dy, res, y, dx, stats, ws, sums
+    return out
 
 
 def cpu_baseline(w):
