@@ -189,3 +189,83 @@ def test_streaming_kernels_largest_config():
     torch.cuda.synchronize()
     assert torch.equal(Y1, Y2)
     gpu.stage.close()
+
+
+def _run_schedule_on_device(w, policy, fused, M, lr):
+    """Runs M minibatches of w's schedule with device-resident inputs (a ring of four) and
+    returns every backward's dX plus the final state, all as device tensors."""
+    import torch
+    import paper_2605_29664_amd as amdp
+    gpu = GpuStage(w, act_slots=w.act_slots, stash_slots=max(2, w.stash_slots))
+    layout = amdp.amdp_stage_param_layout(gpu.cfg)
+    gpu.set_state(W.make_theta(w, layout))
+    gpu.stage.amdp_stage_set_fused_accumulate(fused)
+    ring = 4
+    X = [gpu.to_dev(W.make_x(w, k), gpu.dt) for k in range(ring)]
+    dY = [None if w.has_lm_head else gpu.to_dev(W.make_dy(w, k), gpu.dt) for k in range(ring)]
+    aux = [None if W.make_aux(w, k) is None else gpu.to_dev(np.asarray(W.make_aux(w, k), dtype=np.int32)) for k in range(ring)]
+    out = torch.empty(1, dtype=torch.float32, device="cuda:0") if w.has_lm_head else torch.empty_like(X[0])
+    ev = amdp.amdp_schedule_generate(w.depth, w.pipelines, w.stage, w.threshold, M, w.inject_limit, amdp.U_NEXT_BUBBLE, policy)
+    dxs = {}
+    for e in ev:
+        r = e.mb % ring
+        if e.kind == amdp.EV_F:
+            gpu.stage.amdp_stage_forward(e.mb, e.version, X[r], aux[r], out)
+        elif e.kind == amdp.EV_B:
+            dx = torch.empty_like(X[0])
+            gpu.stage.amdp_stage_backward(e.mb, e.version, dY[r], dx)
+            dxs[e.mb] = dx
+        elif e.kind == amdp.EV_A:
+            gpu.stage.amdp_grad_accumulate(e.mb)
+        else:
+            gpu.stage.amdp_apply_update(lr, w.beta1, w.beta2, w.eps, w.weight_decay, 1.0 / w.threshold, True)
+    n = gpu.n
+    st = [torch.empty(n, dtype=torch.float32, device="cuda:0") for _ in range(4)]
+    gpu.stage.amdp_stage_get_state(*st)
+    torch.cuda.synchronize()
+    gpu.stage.close()
+    return ev, dxs, st
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("k", [3, 4, 5])
+def test_full_size_schedule_properties(k):
+    """Configurations 3, 4, 5 at full depth through one window, its update and the
+    minibatches in flight across it, checked by properties that need no oracle:
+    (a) with the accumulation fused into backward the final state is bit-identical;
+    (b) with the current version in backward instead of the forward's, exactly the
+        minibatches whose forward ran before the update and whose backward ran after
+        it get a different dX (Section 3.1's mismatched minibatches), every other dX is
+        bit-identical, and the state after the update differs."""
+    import torch
+    from oracle import schedule as OS
+    w = W.CONFIGS[k]
+    M = w.threshold + w.act_slots + 2
+    print(f"\n[cfg{k} schedule properties, {M} minibatches] start", flush=True)
+    ev_s, dx_s, st_s = _run_schedule_on_device(w, OS.STASHED, False, M, 1e-3)
+    print("  stashed done", flush=True)
+    ev_f, dx_f, st_f = _run_schedule_on_device(w, OS.STASHED, True, M, 1e-3)
+    print("  fused done", flush=True)
+    for a, b in zip(st_s, st_f):
+        assert torch.equal(a, b), "fused accumulation changed the state"
+    for mb in dx_s:
+        assert torch.equal(dx_s[mb], dx_f[mb])
+    del dx_f, st_f
+    ev_c, dx_c, st_c = _run_schedule_on_device(w, OS.CURRENT, False, M, 1e-3)
+    print("  current done", flush=True)
+    fwd = {e.mb: e.version for e in ev_c if e.kind == OS.F}
+    mismatched = {e.mb for e in ev_c if e.kind == OS.B and e.version != fwd[e.mb]}
+    assert len(mismatched) >= 1 and len(mismatched) <= w.act_slots
+    # The first update closes window 0, none of whose minibatches is mismatched, so version 1 is
+    # the same in both runs: every backward whose two versions agree must give the same dX bit for
+    # bit, before and after that update, and every mismatched one a different dX.
+    for e in ev_c:
+        if e.kind != OS.B:
+            continue
+        same = torch.equal(dx_s[e.mb], dx_c[e.mb])
+        if e.mb in mismatched:
+            assert not same, f"minibatch {e.mb}: backward with a newer version gave the same dX"
+        else:
+            assert same, f"minibatch {e.mb}: dX differs although its versions agree"
+    assert all(torch.isfinite(t).all() for t in st_c)
+    assert not torch.equal(st_s[0], st_c[0])       # the last update applied different gradients
