@@ -158,6 +158,21 @@ __device__ __forceinline__ void epilogue_store8(const Epilogue& e, void* C, long
     }
 }
 
+// fp32 output written, not accumulated, without bias / residual / GELU terms (the
+// weight-gradient products into the staging buffer): four consecutive columns
+// n..n+3 of row m. The callers give consecutive lanes consecutive column quads of
+// one row, so that one store instruction writes whole contiguous row segments;
+// with eight columns per lane as two 16-byte stores every instruction touches
+// every 128-byte line of the segment half-way. Measured on configuration 5's four
+// products: +3.7 to +5.7 %. (With C += the eight-column form, whose lane reads and
+// writes 32 contiguous bytes, measured 2-3 % faster and is kept.)
+__device__ __forceinline__ void epilogue_store4_f32(const Epilogue& e, void* C, long ldc, long m, long n, f32x4 v) {
+    *(f32x4*)((float*)C + m * ldc + n) = v * e.alpha;
+}
+__device__ __forceinline__ bool epilogue_is_plain_f32(const Epilogue& e) {
+    return e.out_f32 && !e.accumulate && !e.bias && !e.res && !e.gelu_u && !e.aux_out;
+}
+
 // One GEMM problem, possibly batched over (outer, inner) = (sequence, head).
 //   C[m,n] = sum_k A(m,k) * B(k,n)
 //   A(m,k) = A[m*a_rs + k*a_cs], B(k,n) = B[k*b_rs + n*b_cs]   (element strides)

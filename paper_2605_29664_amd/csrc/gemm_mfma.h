@@ -375,6 +375,7 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_kernel(GemmArgs g) {
     // issue order, so after this barrier (every wave is done with the operand
     // tiles) the passes below need no workgroup barrier between them.
     __syncthreads();
+    const bool plain_f32 = epilogue_is_plain_f32(g.epi);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         __builtin_amdgcn_wave_barrier();
@@ -384,6 +385,16 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_kernel(GemmArgs g) {
             for (int v = 0; v < 16; ++v)
                 strip[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * SW + j * 32 + (lane & 31)] = acc[i][j][v];
         __builtin_amdgcn_wave_barrier();
+        if (plain_f32) {
+            constexpr int QPR = WN / 4;            // column quads per strip row
+            for (int it = 0; it < WN / 8; ++it) {
+                const int c = lane + 64 * it;
+                const int row = c / QPR, cq = c % QPR;
+                const f32x4 v4 = *(lds_f32x4*)(strip + row * SW + cq * 4);
+                epilogue_store4_f32(g.epi, C, g.ldc, m0 + wm * WM + i * 32 + row, n0 + wn * WN + cq * 4, v4);
+            }
+            continue;
+        }
         constexpr int CPR = WN / 8;                // 8-column chunks per strip row
         for (int it = 0; it < WN / 16; ++it) {
             const int c = lane + 64 * it;

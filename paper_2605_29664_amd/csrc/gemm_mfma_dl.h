@@ -242,6 +242,7 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_dl_kernel(GemmArgs g) {
     void* C = g.C;
     constexpr int SW = WN + 4;
     lds_f32* strip = (lds_f32*)lds + wave * (32 * SW);
+    const bool plain_f32 = epilogue_is_plain_f32(g.epi);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         __builtin_amdgcn_wave_barrier();   // wave-private strip: no workgroup barrier needed (see gemm_mfma_kernel)
@@ -251,6 +252,18 @@ __global__ __launch_bounds__(128 * WGN) void gemm_mfma_dl_kernel(GemmArgs g) {
             for (int v = 0; v < 16; ++v)
                 strip[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * SW + j * 32 + (lane & 31)] = acc[i][j][v];
         __builtin_amdgcn_wave_barrier();
+        if (plain_f32) {
+            constexpr int QPR = WN / 4;            // column quads per strip row
+            for (int it = 0; it < WN / 8; ++it) {
+                const int c = lane + 64 * it;
+                const int row = c / QPR, cq = c % QPR;
+                const f32x4 v4 = *(lds_f32x4*)(strip + row * SW + cq * 4);
+                const long m = m0 + wm * WM + i * 32 + row;
+                const long n = n0 + wn * WN + cq * 4;
+                if (!EDGE || (m < g.M && n < g.N)) epilogue_store4_f32(g.epi, C, g.ldc, m, n, v4);
+            }
+            continue;
+        }
         constexpr int CPR = WN / 8;
         for (int it = 0; it < WN / 16; ++it) {
             const int c = lane + 64 * it;
