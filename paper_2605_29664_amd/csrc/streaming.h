@@ -138,6 +138,38 @@ __global__ __launch_bounds__(ACC_BLOCK) void splitk_reduce_kernel(float* __restr
     o4[i] = s;
 }
 
+// out[m][n] = bf16(partial[0][m][n] + ... + partial[parts-1][m][n] (+ bias[n]) (+ res[m][n])), eight
+// columns per lane; n8 = M*N/8, N a multiple of 8, out and res row-major [M, N]. The second stage of a
+// bf16-output product whose contraction was split in parts; parts are added in index order.
+__global__ __launch_bounds__(ACC_BLOCK) void splitk_epilogue_kernel(bf16* __restrict__ out,
+                                                                    const float* __restrict__ partial,
+                                                                    const bf16* __restrict__ bias,
+                                                                    const bf16* __restrict__ res, long n8, int N,
+                                                                    int parts) {
+    const long i = (long)blockIdx.x * ACC_BLOCK + threadIdx.x;
+    if (i >= n8) return;
+    const f32x4* p4 = (const f32x4*)partial;
+    f32x4 lo = p4[2 * i], hi = p4[2 * i + 1];
+    for (int k = 1; k < parts; ++k) {
+        lo += p4[(long)k * 2 * n8 + 2 * i];
+        hi += p4[(long)k * 2 * n8 + 2 * i + 1];
+    }
+    if (bias) {
+        const bf16x8 b = *(const bf16x8*)(bias + (i * 8) % N);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { lo[k] += (float)b[k]; hi[k] += (float)b[4 + k]; }
+    }
+    if (res) {
+        const bf16x8 r = ((const bf16x8*)res)[i];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { lo[k] += (float)r[k]; hi[k] += (float)r[4 + k]; }
+    }
+    bf16x8 o;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { o[k] = (bf16)lo[k]; o[4 + k] = (bf16)hi[k]; }
+    ((bf16x8*)out)[i] = o;
+}
+
 // grid for the grid-stride helpers (copy, zero, publish)
 inline int stream_grid(long n4) {
     long blocks = (n4 + STREAM_BLOCK - 1) / STREAM_BLOCK;

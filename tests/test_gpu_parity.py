@@ -9,7 +9,7 @@ import workloads as W
 from oracle import schedule as OSched
 from tests.parity import run_parity, worst_entries, GpuStage, rel_err, TOL
 from paper_2605_29664_amd.binding import (OPT_GEMM_TILE, OPT_GEMM_TRANSPOSING_READS, OPT_GEMM_DIRECT_TO_LDS,
-                                          OPT_LAZY_JOIN, OPT_SPLIT_K_MIN_TOKENS, ATTN_UNFUSED)
+                                          OPT_LAZY_JOIN, OPT_SPLIT_K_MIN_TOKENS, OPT_SPLIT_MAIN_MIN_K, ATTN_UNFUSED)
 
 pytestmark = pytest.mark.gpu
 
@@ -138,6 +138,31 @@ def test_weight_gradients_split_over_tokens(key):
     assert np.array_equal(sums[0], sums[1]) and np.array_equal(sums[0], sums[2])
     assert not np.array_equal(sums[0], sums[3]), "the split path did not run"      # another summation order
     assert rel_err(sums[0], sums[3]) < 1e-5
+
+
+@pytest.mark.parametrize("key", ["gpt_tile", "bert_tile", "lmhead_tile"])
+def test_main_chain_products_with_split_contraction(key):
+    """Products of the forward / dX chain with few 256x256 tiles and a long
+    contraction run in two halves into fp32 scratch, added in order with bias and
+    residual by a second kernel. At the tile test shapes that needs the minimum
+    half lowered to 64 (default 4096); the profile shows that the path ran."""
+    import torch
+    w = W.TINY[key]
+    rep = run_parity(w, n_windows=1, verbose=False, options={OPT_SPLIT_MAIN_MIN_K: 64})
+    _report(f"{key}_split_main", rep)
+    assert rep["ok"], worst_entries(rep)
+    from oracle.stage import Stage as OStage
+    gpu = GpuStage(w, act_slots=2, stash_slots=1, options={OPT_SPLIT_MAIN_MIN_K: 64})
+    gpu.set_state(W.make_theta(w, OStage.from_workload(w).layout))
+    gpu.stage.amdp_stage_profile_begin()
+    gpu.forward(0, 0, W.make_x(w, 0), W.make_aux(w, 0))
+    gpu.backward(0, 0, None if w.has_lm_head else W.make_dy(w, 0))
+    prof = gpu.stage.amdp_stage_profile_end()
+    split = {k: v["launches"] for k, v in prof.items() if k.endswith("_splitk")}
+    assert split.get("gemm_mfma256x256_NN_splitk", 0) >= 2 * w.n_layers, prof.keys()   # QKV and out-projection at least
+    assert split.get("gemm_mfma256x256_NT_splitk", 0) >= 2 * w.n_layers, prof.keys()   # dX of W_1, W_o (and W_qkv)
+    assert prof["splitk_reduce"]["launches"] == sum(split.values())
+    gpu.stage.close()
 
 
 @pytest.mark.parametrize("key", ["gpt_tile64", "bert_dh50", "bert_tile_dh50", "gpt_tile_dh96"])
