@@ -16,6 +16,7 @@
 #pragma once
 #include "common.h"
 #include "gemm_mfma.h"
+#include <type_traits>
 
 namespace amdp {
 
@@ -354,20 +355,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 
                 sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_row<STRIDE>(tQ, qt * 32, kk, lane), bk[kk], sc, 0, 0, 0);
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_row<STRIDE>(tdO, qt * 32, kk, lane), bv[kk], dp, 0, 0, 0);
             }
+            // masks only where this wave's keys meet the diagonal or the padding edge
+            // (wave-uniform test): elsewhere one fma, one exp2, one sub, one mul per score
+            const bool edge = CAUSAL ? (q0 + qt * 32 < k_wave + 31) : (k_wave + 31 >= klimit);
+            auto probabilities = [&](auto masked) {
 #pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const f32x4 l4 = *(const f32x4*)&sstat[0][qt * 32 + 8 * gq + 4 * half];
-                const f32x4 d4 = *(const f32x4*)&sstat[1][qt * 32 + 8 * gq + 4 * half];
+                for (int gq = 0; gq < 4; ++gq) {
+                    const f32x4 l4 = *(const f32x4*)&sstat[0][qt * 32 + 8 * gq + 4 * half];
+                    const f32x4 d4 = *(const f32x4*)&sstat[1][qt * 32 + 8 * gq + 4 * half];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int v = 4 * gq + e;
-                    const int q = q0 + qt * 32 + 8 * gq + 4 * half + e;
-                    float p = exp2_raw(fmaf(sc[v], sl2, -l4[e]));
-                    if ((CAUSAL && key > q) || key_dead) p = 0.f;
-                    sc[v] = p;
-                    dp[v] = p * (dp[v] - d4[e]);         // the factor `scale` of dS is applied to dK at the end
+                    for (int e = 0; e < 4; ++e) {
+                        const int v = 4 * gq + e;
+                        float p = exp2_raw(fmaf(sc[v], sl2, -l4[e]));
+                        if constexpr (decltype(masked)::value) {
+                            const int q = q0 + qt * 32 + 8 * gq + 4 * half + e;
+                            if ((CAUSAL && key > q) || key_dead) p = 0.f;
+                        }
+                        sc[v] = p;
+                        dp[v] = p * (dp[v] - d4[e]);     // the factor `scale` of dS is applied to dK at the end
+                    }
                 }
-            }
+            };
+            if (edge) probabilities(std::true_type{}); else probabilities(std::false_type{});
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
                 const bf16x8 pb = pack8(sc, 8 * ks), dsb = pack8(dp, 8 * ks);
@@ -447,13 +456,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
                 sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_row<STRIDE>(tK, kt * 32, kk, lane), bq[kk], sc, 0, 0, 0);
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_row<STRIDE>(tV, kt * 32, kk, lane), bdo[kk], dp, 0, 0, 0);
             }
+            // masks only where the key tile meets this wave's diagonal or the padding edge (wave-uniform)
+            const bool edge = CAUSAL ? (k0 + kt * 32 + 31 > q_wave) : (k0 + kt * 32 + 31 >= klimit);
+            auto dscores = [&](auto masked) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int key = k0 + kt * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                float p = exp2_raw(fmaf(sc[v], sl2, -lse_q));
-                if ((CAUSAL && key > q) || (!CAUSAL && key >= klimit)) p = 0.f;   // causal stages carry no padding mask
-                dp[v] = p * (dp[v] - delta_q);           // the factor `scale` of dS is applied to dQ at the end
-            }
+                for (int v = 0; v < 16; ++v) {
+                    float p = exp2_raw(fmaf(sc[v], sl2, -lse_q));
+                    if constexpr (decltype(masked)::value) {
+                        const int key = k0 + kt * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                        if ((CAUSAL && key > q) || (!CAUSAL && key >= klimit)) p = 0.f;   // causal stages carry no padding mask
+                    }
+                    dp[v] = p * (dp[v] - delta_q);       // the factor `scale` of dS is applied to dQ at the end
+                }
+            };
+            // (at head dimension 128 the second copy of the loop body costs 14 spilled registers
+            // and 13 % of the kernel's time: there every tile takes the masked form)
+            if (DH == 128 || edge) dscores(std::true_type{}); else dscores(std::false_type{});
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
                 const bf16x8 dsb = pack8(dp, 8 * ks);
