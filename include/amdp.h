@@ -459,7 +459,7 @@ int amdp_device_copy(void* dst, const void* src, size_t bytes, void* hip_stream)
  *                                    tiles cover at most half of the compute units runs with its
  *                                    contraction split in two halves, added in order by a second
  *                                    kernel together with bias and residual, when a half is at least
- *                                    this long (default 4096, at least 64; a large value switches it off) */
+ *                                    this long (default 3072, at least 64; a large value switches it off) */
 enum { AMDP_OPT_GEMM_TILE = 0, AMDP_OPT_GEMM_TRANSPOSING_READS = 1, AMDP_OPT_GEMM_DIRECT_TO_LDS = 2,
        AMDP_OPT_LAZY_JOIN = 3, AMDP_OPT_SPLIT_K_MIN_TOKENS = 4, AMDP_OPT_SPLIT_MAIN_MIN_K = 5 };
 int amdp_stage_set_option(amdp_stage_t* stage, int32_t option, int32_t value);

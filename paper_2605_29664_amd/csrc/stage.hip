@@ -266,7 +266,7 @@ struct amdp_stage {
     bool overlap = true;
     bool fused_acc = false;        // backward adds parameter gradients into G directly
     int splitk_min_k = 512;        // fewest tokens a part of a split weight-gradient product contracts
-    int split_main_min_k = 4096;   // shortest half of a main-chain contraction that is worth splitting
+    int split_main_min_k = 3072;   // shortest half of a main-chain contraction that is worth splitting
     bool flash = true;      // fused attention kernels (shape permitting); false: scores, softmax, probabilities in HBM
     hipEvent_t next_event() { ev_next = (ev_next + 1) % 16; return events[ev_next]; }
 
@@ -446,7 +446,9 @@ enum GemmLayout { G_NN, G_NT, G_TN };
 // scratch), and a second kernel adds the parts in order and applies bias and
 // residual. Measured on configuration 5's 2048 x 4096 outputs with operands that
 // are not cache-resident, against the 128x128 tile at two workgroups per unit:
-// +15 to +19 % at contractions of 12288 and 16384, -6 to -10 % at 4096.
+// +15 to +19 % at contractions of 12288 and 16384, -6 to -10 % at 4096; on
+// configuration 4's 4096 x 2048 outputs +0.5 to +13 % at 8192, +6 to +7 % at 6144,
+// -22 to -25 % at 2048. Hence: a half must be at least 3072 long.
 int main_split(const amdp_stage* st, const GemmArgs& g, bool a_km, bool b_km) {
     if (!st->d.bf || st->force_tile != 0 || g.batch != 1 || g.causal || g.epi.out_f32 || g.epi.gelu_u || g.epi.aux_out)
         return 1;

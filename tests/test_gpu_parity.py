@@ -145,7 +145,7 @@ def test_main_chain_products_with_split_contraction(key):
     """Products of the forward / dX chain with few 256x256 tiles and a long
     contraction run in two halves into fp32 scratch, added in order with bias and
     residual by a second kernel. At the tile test shapes that needs the minimum
-    half lowered to 64 (default 4096); the profile shows that the path ran."""
+    half lowered to 64 (default 3072); the profile shows that the path ran."""
     import torch
     w = W.TINY[key]
     rep = run_parity(w, n_windows=1, verbose=False, options={OPT_SPLIT_MAIN_MIN_K: 64})
