@@ -27,9 +27,9 @@ __global__ __launch_bounds__(ACC_BLOCK) void accumulate_kernel(float* __restrict
     const long i = (long)blockIdx.x * ACC_BLOCK + threadIdx.x;
     if (i >= n4) return;
     f32x4* G4 = (f32x4*)G;
-    const f32x4 a = G4[i];
+    const f32x4 a = __builtin_nontemporal_load(&G4[i]);
     const f32x4 b = __builtin_nontemporal_load(&((const f32x4*)g)[i]);
-    G4[i] = a + b;
+    __builtin_nontemporal_store(a + b, &G4[i]);
 }
 
 struct AdamScalars {
