@@ -384,10 +384,33 @@ def cpu_baseline(w):
     optim.adam_step(theta, np.zeros_like(theta), np.zeros_like(theta), G, 1, w.lr, w.beta1, w.beta2, w.eps)
     t2 = time.perf_counter()
     per_mb = (t1 - t0) / n_mb + (t2 - t1) / w.threshold
-    return {"value": w.tokens / per_mb, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+    scalar = scalar_loop_tier()
+    return {"scalar_loop_tier": scalar, "value": w.tokens / per_mb, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
             "sample": f"{n_mb} minibatch(es) of {w.tokens} tokens forward+backward+accumulate in fp64 numpy "
                       f"({t1 - t0:.1f} s) + 1/{w.threshold} of one Adam step ({t2 - t1:.2f} s)",
             "host_cpus": os.cpu_count()}
+
+
+def scalar_loop_tier():
+    """The oracle's second tier (plain C loops over scalars, fp64, one thread) on
+    configuration 1, the only benchmark configuration it finishes in seconds:
+    forward + backward of whole minibatches for about two seconds."""
+    import numpy as np
+    import workloads as W
+    from oracle.slow import SlowStage
+    w = W.get("1")
+    sl = SlowStage.from_workload(w)
+    from oracle.stage import param_layout
+    theta = W.make_theta(w, param_layout(w.n_layers, w.d_model, w.d_ffn)).astype(np.float64)
+    n_mb, t0 = 0, time.perf_counter()
+    while n_mb == 0 or (n_mb < 64 and time.perf_counter() - t0 < 2.0):
+        x, dy = W.make_x(w, n_mb).astype(np.float64), W.make_dy(w, n_mb).astype(np.float64)
+        _, saved = sl.forward(theta, x)
+        sl.backward(theta, saved, dy)
+        n_mb += 1
+    dt = time.perf_counter() - t0
+    return {"value": n_mb * w.tokens / dt, "unit": "tokens/s", "cores": 1, "workload": w.name,
+            "sample": f"{n_mb} minibatch(es) of {w.tokens} tokens forward+backward in fp64 C loops ({dt:.2f} s)"}
 
 
 if __name__ == "__main__":

@@ -12,7 +12,10 @@ only by tests, by the smoke check and by the benchmark's cpu_baseline leg;
 the product path never calls it.
 
 Arithmetic is numpy float64 throughout; numpy matmul, scipy's erf and numpy's
-elementwise functions are the only library primitives used as steps.
+elementwise functions are the only library primitives used as steps. A second
+tier of the stage's forward and backward (slow_stage.c, loaded by slow.py)
+repeats the same definitions as plain C loops over scalars, libm only; the
+two tiers are compared with each other in the tests.
 
 Pins (see tests, all runnable without a GPU):
   schedule.generate   Lemma 1 closed form via an independent discrete-event
@@ -21,6 +24,8 @@ Pins (see tests, all runnable without a GPU):
   stage forward       torch.nn.functional fp64 reference ops; causality and
                       padding-independence properties.
   stage backward      central finite differences; torch.autograd fp64.
+  scalar-loop tier    the numpy tier (written separately), to 1e-11 of each
+                      tensor's largest entry, on tiny shapes and configuration 1.
   accumulate          sum-of-per-minibatch-gradients invariant.
   adam                closed form of the first step; torch.optim.Adam fp64;
                       the bias-correction-free form printed in Appendix B.1.
