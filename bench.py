@@ -85,7 +85,8 @@ def main():
     T, P = w.threshold, w.pipelines
     K, Wu = args.steps, args.warmup
     inflight = w.act_slots
-    M = (Wu + K + 3 + min(K, 3)) * T + inflight      # warm-up, timed, 2 profiled, a few steps with fused accumulation
+    # warm-up, timed, 2 profiled, a few steps on one stream, a few with fused accumulation
+    M = (Wu + K + 3 + 2 * min(K, 3)) * T + inflight
 
     cfg = amdp.make_config(**W.stage_config_args(w))
     stage = amdp.Stage(cfg, device="cuda:0")
@@ -291,6 +292,21 @@ def main():
     # (three steps at most: under a kernel trace of this command the launches of this leg, whose
     # weight-gradient products read and write the sum, would otherwise shift every average)
     Kf = min(K, 3)
+    # ---- the same steps with everything on the caller's stream (same box, same process):
+    # what the side stream is worth on this workload ---------------------------------------
+    if stage.amdp_stage_get_overlap() and len(steps) >= cursor + 2 * Kf:
+        form = stage.amdp_stage_get_overlap()
+        stage.amdp_stage_set_overlap(0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(cursor, cursor + Kf):
+            run_step(steps[i])
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        cursor += Kf
+        stage.amdp_stage_set_overlap(form)
+        result["single_stream"] = {"value": Kf * T * w.tokens / el, "unit": "tokens/s", "ms_per_step": 1e3 * el / Kf,
+                                   "steps": Kf, "note": "amdp_stage_set_overlap(0): every kernel on the caller's stream"}
     if not args.fused_accumulate and len(steps) >= cursor + Kf:
         stage.amdp_stage_set_fused_accumulate(True)
         torch.cuda.synchronize()
