@@ -459,9 +459,17 @@ int amdp_device_copy(void* dst, const void* src, size_t bytes, void* hip_stream)
  *                                    tiles cover at most half of the compute units runs with its
  *                                    contraction split in two halves, added in order by a second
  *                                    kernel together with bias and residual, when a half is at least
- *                                    this long (default 3072, at least 64; a large value switches it off) */
+ *                                    this long (default 3072, at least 64; a large value switches it off)
+ *   AMDP_OPT_LEAF_FORKS              with the side stream on, how often per layer a backward hands its
+ *                                    parameter-gradient work to the side stream: 0 once per product
+ *                                    (default below d_model 2048: every product starts as early as it
+ *                                    can), 2 after the MLP half and at the end of the layer (default
+ *                                    from d_model 2048 on), 1 at the end of the layer only. Each
+ *                                    hand-over costs the host two event calls and a change of the
+ *                                    stream it enqueues on, about 20 us; results are bit-identical */
 enum { AMDP_OPT_GEMM_TILE = 0, AMDP_OPT_GEMM_TRANSPOSING_READS = 1, AMDP_OPT_GEMM_DIRECT_TO_LDS = 2,
-       AMDP_OPT_LAZY_JOIN = 3, AMDP_OPT_SPLIT_K_MIN_TOKENS = 4, AMDP_OPT_SPLIT_MAIN_MIN_K = 5 };
+       AMDP_OPT_LAZY_JOIN = 3, AMDP_OPT_SPLIT_K_MIN_TOKENS = 4, AMDP_OPT_SPLIT_MAIN_MIN_K = 5,
+       AMDP_OPT_LEAF_FORKS = 6 };
 int amdp_stage_set_option(amdp_stage_t* stage, int32_t option, int32_t value);
 
 /* The input embedding of the first stage and the output projection of the last

@@ -15,6 +15,6 @@ from .binding import (  # noqa: F401
     Stage,
     EV_F, EV_B, EV_A, EV_U, U_NEXT_BUBBLE, U_EAGER, BWD_STASHED, BWD_CURRENT,
     FLAG_LAST_USE, FLAG_PARTIAL_WINDOW, BLOCK_GPT, BLOCK_BERT, FP32, BF16, ATTN_AUTO, ATTN_UNFUSED,
-    OPT_GEMM_TILE, OPT_GEMM_TRANSPOSING_READS, OPT_GEMM_DIRECT_TO_LDS, OPT_LAZY_JOIN, OPT_SPLIT_K_MIN_TOKENS, OPT_SPLIT_MAIN_MIN_K,
+    OPT_GEMM_TILE, OPT_GEMM_TRANSPOSING_READS, OPT_GEMM_DIRECT_TO_LDS, OPT_LAZY_JOIN, OPT_SPLIT_K_MIN_TOKENS, OPT_SPLIT_MAIN_MIN_K, OPT_LEAF_FORKS,
     E_INVAL, E_MB_STATE, E_NO_SLOT, E_VERSION, E_STASH_FULL, E_HIP, E_CAPACITY,
 )

@@ -16,7 +16,7 @@ FLAG_LAST_USE, FLAG_PARTIAL_WINDOW = 1, 2
 BLOCK_GPT, BLOCK_BERT = 0, 1
 FP32, BF16 = 0, 1
 ATTN_AUTO, ATTN_UNFUSED = 0, 1
-OPT_GEMM_TILE, OPT_GEMM_TRANSPOSING_READS, OPT_GEMM_DIRECT_TO_LDS, OPT_LAZY_JOIN, OPT_SPLIT_K_MIN_TOKENS, OPT_SPLIT_MAIN_MIN_K = 0, 1, 2, 3, 4, 5
+OPT_GEMM_TILE, OPT_GEMM_TRANSPOSING_READS, OPT_GEMM_DIRECT_TO_LDS, OPT_LAZY_JOIN, OPT_SPLIT_K_MIN_TOKENS, OPT_SPLIT_MAIN_MIN_K, OPT_LEAF_FORKS = 0, 1, 2, 3, 4, 5, 6
 E_INVAL, E_MB_STATE, E_NO_SLOT, E_VERSION, E_STASH_FULL, E_HIP, E_CAPACITY = -1, -2, -3, -4, -5, -6, -7
 E_TOO_LARGE = -8
 

@@ -264,6 +264,7 @@ struct amdp_stage {
     uint64_t free_seq[MAX_ASLOTS] = {};
     uint64_t free_counter = 0;
     bool overlap = true;
+    int leaf_forks = 0;            // side-stream forks per layer of a backward: 0 = one per leaf, 1, 2 (set at creation)
     bool fused_acc = false;        // backward adds parameter gradients into G directly
     int splitk_min_k = 512;        // fewest tokens a part of a split weight-gradient product contracts
     int split_main_min_k = 3072;   // shortest half of a main-chain contraction that is worth splitting
@@ -1057,44 +1058,66 @@ int backward_impl(amdp_stage* st, int aslot, int vslot, const int32_t* valid, co
         const float* st1 = (const float*)(S + a.st1);
         const float* st2 = (const float*)(S + a.st2);
         ColSumList cs(d.N);
+        // Weight-gradient products wait in `jobs` until the next fork: switching the
+        // stream the host enqueues on costs more than ten launches, so a layer's leaves
+        // go to the side stream in one or two groups. Nothing a leaf reads is
+        // rewritten before the layer ends (the scratch is per layer).
+        struct DwJob { const void* x; const void* dy; float* dw; int n, out, in; };
+        DwJob jobs[4];
+        int n_jobs = 0;
+        auto flush_dw = [&](bool with_colsums) -> int {
+            if (n_jobs == 0 && !with_colsums) return AMDP_OK;
+            LEAF({
+                for (int j = 0; j < n_jobs; ++j)
+                    TRY(linear_dw(st, jobs[j].x, jobs[j].dy, jobs[j].dw, jobs[j].n, jobs[j].out, jobs[j].in));
+                if (with_colsums) TRY(colsum_flush<T>(st, cs));
+            });
+            n_jobs = 0;
+            return AMDP_OK;
+        };
+        auto leaf_dw = [&](const void* x, const void* dy, float* dw, int n, int out, int in, bool mid_layer) -> int {
+            jobs[n_jobs++] = DwJob{x, dy, dw, n, out, in};
+            if (!st->overlap || st->leaf_forks == 0 || (mid_layer && st->leaf_forks == 2)) return flush_dw(false);
+            return AMDP_OK;
+        };
 
         if (d.causal) {
             // y = y1 + MLP(LN2(y1))
             colsum_add<T>(cs, dcur, nullptr, nullptr, G(B_2), d.D);
-            LEAF({ TRY(linear_dw(st, S + a.h, dcur, G(W_2), d.N, d.D, d.F)); });
+            TRY(leaf_dw(S + a.h, dcur, G(W_2), d.N, d.D, d.F, false));
             TRY(linear_dx(st, dcur, P(W_2), S + a.u, nullptr, dffn, d.N, d.D, d.F));
             colsum_add<T>(cs, dffn, nullptr, nullptr, G(B_1), d.F);
-            LEAF({ TRY(linear_dw(st, S + a.c, dffn, G(W_1), d.N, d.F, d.D)); });
+            TRY(leaf_dw(S + a.c, dffn, G(W_1), d.N, d.F, d.D, true));
             TRY(linear_dx(st, dffn, P(W_1), nullptr, nullptr, ta, d.N, d.F, d.D));          // ta = dc
             TRY(ln_bwd_pg<T>(st, cs, ta, S + a.y1, st2, P(LN2_G), dcur, tb, G(LN2_G)));   // tb = dy1
             // y1 = x + Attn(LN1(x))
             colsum_add<T>(cs, tb, nullptr, nullptr, G(B_O), d.D);
-            LEAF({ TRY(linear_dw(st, S + a.o, tb, G(W_O), d.N, d.D, d.D)); });
+            TRY(leaf_dw(S + a.o, tb, G(W_O), d.N, d.D, d.D, false));
             TRY(linear_dx(st, tb, P(W_O), nullptr, nullptr, dO, d.N, d.D, d.D));
             TRY(attention_bwd<T>(st, dO, S + a.qkv, S + a.P, S + a.o, dP, dqkv, valid));
             colsum_add<T>(cs, dqkv, nullptr, nullptr, G(B_QKV), 3 * d.D);
-            LEAF({ TRY(linear_dw(st, S + a.a, dqkv, G(W_QKV), d.N, 3 * d.D, d.D)); });
+            TRY(leaf_dw(S + a.a, dqkv, G(W_QKV), d.N, 3 * d.D, d.D, false));
             TRY(linear_dx(st, dqkv, P(W_QKV), nullptr, nullptr, tc, d.N, 3 * d.D, d.D));     // tc = da
             TRY(ln_bwd_pg<T>(st, cs, tc, S + a.xin, st1, P(LN1_G), tb, dnext, G(LN1_G)));
         } else {
             // y = LN2(r2), r2 = y1 + MLP(y1); y1 = LN1(r1), r1 = x + Attn(x)
             TRY(ln_bwd_pg<T>(st, cs, dcur, S + a.c, st2, P(LN2_G), nullptr, ta, G(LN2_G)));   // ta = dr2
             colsum_add<T>(cs, ta, nullptr, nullptr, G(B_2), d.D);
-            LEAF({ TRY(linear_dw(st, S + a.h, ta, G(W_2), d.N, d.D, d.F)); });
+            TRY(leaf_dw(S + a.h, ta, G(W_2), d.N, d.D, d.F, false));
             TRY(linear_dx(st, ta, P(W_2), S + a.u, nullptr, dffn, d.N, d.D, d.F));
             colsum_add<T>(cs, dffn, nullptr, nullptr, G(B_1), d.F);
-            LEAF({ TRY(linear_dw(st, S + a.y1, dffn, G(W_1), d.N, d.F, d.D)); });
+            TRY(leaf_dw(S + a.y1, dffn, G(W_1), d.N, d.F, d.D, true));
             TRY(linear_dx(st, dffn, P(W_1), nullptr, ta, tb, d.N, d.F, d.D));               // tb = dy1
             TRY(ln_bwd_pg<T>(st, cs, tb, S + a.a, st1, P(LN1_G), nullptr, tc, G(LN1_G)));     // tc = dr1
             colsum_add<T>(cs, tc, nullptr, nullptr, G(B_O), d.D);
-            LEAF({ TRY(linear_dw(st, S + a.o, tc, G(W_O), d.N, d.D, d.D)); });
+            TRY(leaf_dw(S + a.o, tc, G(W_O), d.N, d.D, d.D, false));
             TRY(linear_dx(st, tc, P(W_O), nullptr, nullptr, dO, d.N, d.D, d.D));
             TRY(attention_bwd<T>(st, dO, S + a.qkv, S + a.P, S + a.o, dP, dqkv, valid));
             colsum_add<T>(cs, dqkv, nullptr, nullptr, G(B_QKV), 3 * d.D);
-            LEAF({ TRY(linear_dw(st, S + a.xin, dqkv, G(W_QKV), d.N, 3 * d.D, d.D)); });
+            TRY(leaf_dw(S + a.xin, dqkv, G(W_QKV), d.N, 3 * d.D, d.D, false));
             TRY(linear_dx(st, dqkv, P(W_QKV), nullptr, tc, dnext, d.N, 3 * d.D, d.D));
         }
-        LEAF({ TRY(colsum_flush<T>(st, cs)); });
+        TRY(flush_dw(true));
         // the leaves of this layer read the caller's dY: remember where they end
         if (dcur == dY && dY && st->overlap) {
             HIP_TRY(hipEventRecord(st->input_ev, st->side));
@@ -1225,6 +1248,13 @@ extern "C" int amdp_stage_create(const amdp_stage_config_t* cfg, void* workspace
     // unit with a 256x256 tile, concurrent kernels only share the units (measured: no
     // gain at D = 4096, 3 % at 2048, 11 % at 1024), so it is off by default there.
     st->overlap = (long)(st->d.D / 256) * (st->d.D / 256) < st->n_cu;
+    // Handing work to the side stream costs the host about 20 us each time (two event calls and
+    // a change of the stream it enqueues on). One hand-over per product starts every leaf as
+    // early as possible; two per layer cost the host half as much per backward. Measured per
+    // step, GPU / host: D = 1024 causal 18.6 / 7.0 ms against 18.7 / 4.7, D = 1024
+    // bidirectional 26.9 / 10 against 28.1 / 6.9, D = 2048 with LM head 77.0 / 6.8 against
+    // 76.0 / 5.2: grouped from D = 2048 on.
+    st->leaf_forks = st->d.D >= 2048 ? 2 : 0;
     st->flash = cfg->attention == AMDP_ATTN_AUTO;
     // parameter buffers, version slots and the padding behind them start at zero
     if (device_zero(st->launch, st->base, st->w.act) != AMDP_OK) {
@@ -1633,6 +1663,10 @@ extern "C" int amdp_stage_set_option(amdp_stage_t* st, int32_t option, int32_t v
         case AMDP_OPT_SPLIT_MAIN_MIN_K:
             if (value < 64) return AMDP_E_INVAL;
             st->split_main_min_k = value;
+            return AMDP_OK;
+        case AMDP_OPT_LEAF_FORKS:
+            if (value < 0 || value > 2) return AMDP_E_INVAL;
+            st->leaf_forks = value;
             return AMDP_OK;
     }
     return AMDP_E_INVAL;

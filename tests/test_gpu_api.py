@@ -50,7 +50,7 @@ def test_read_version_and_options():
     with pytest.raises(amdp.AmdpError) as ei:
         gpu.stage.amdp_stage_read_version(6, buf)
     assert ei.value.code == amdp.E_VERSION
-    for opt, bad in ((99, 0), (amdp.OPT_GEMM_DIRECT_TO_LDS, 3), (amdp.OPT_SPLIT_K_MIN_TOKENS, 8)):
+    for opt, bad in ((99, 0), (amdp.OPT_GEMM_DIRECT_TO_LDS, 3), (amdp.OPT_SPLIT_K_MIN_TOKENS, 8), (amdp.OPT_LEAF_FORKS, 3)):
         with pytest.raises(amdp.AmdpError) as ei:
             gpu.stage.amdp_stage_set_option(opt, bad)
         assert ei.value.code == amdp.E_INVAL

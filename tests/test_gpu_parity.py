@@ -9,7 +9,7 @@ import workloads as W
 from oracle import schedule as OSched
 from tests.parity import run_parity, worst_entries, GpuStage, rel_err, TOL
 from paper_2605_29664_amd.binding import (OPT_GEMM_TILE, OPT_GEMM_TRANSPOSING_READS, OPT_GEMM_DIRECT_TO_LDS,
-                                          OPT_LAZY_JOIN, OPT_SPLIT_K_MIN_TOKENS, OPT_SPLIT_MAIN_MIN_K, ATTN_UNFUSED)
+                                          OPT_LAZY_JOIN, OPT_SPLIT_K_MIN_TOKENS, OPT_SPLIT_MAIN_MIN_K, OPT_LEAF_FORKS, ATTN_UNFUSED)
 
 pytestmark = pytest.mark.gpu
 
@@ -267,8 +267,10 @@ def test_side_stream_on_off_bit_identical():
     xs = {m: torch.from_numpy(W.make_x(w, m)).to("cuda:0").to(torch.bfloat16) for m in range(24)}
     dys = {m: torch.from_numpy(W.make_dy(w, m)).to("cuda:0").to(torch.bfloat16) for m in range(24)}
     finals = []
-    for overlap, lazy in ((True, 1), (True, 0), (False, 1)):   # lazy 0: every backward ends by joining its leaves
-        gpu = GpuStage(w, act_slots=12, stash_slots=3, options={OPT_LAZY_JOIN: lazy})
+    # lazy 0: every backward ends by joining its leaves; forks: hand-overs to the side stream per layer
+    # (0 = one per product, the default at this width)
+    for overlap, lazy, forks in ((True, 1, 0), (True, 0, 0), (False, 1, 0), (True, 1, 1), (True, 1, 2)):
+        gpu = GpuStage(w, act_slots=12, stash_slots=3, options={OPT_LAZY_JOIN: lazy, OPT_LEAF_FORKS: forks})
         gpu.set_state(theta0)
         assert gpu.stage.amdp_stage_get_overlap()          # narrow stage: the side stream is on by default
         gpu.stage.amdp_stage_set_overlap(overlap)
