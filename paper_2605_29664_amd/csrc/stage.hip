@@ -240,7 +240,7 @@ struct amdp_stage {
     bool use_tr = true;
     int force_tile = 0;
     int use_direct = 1;           // plain products load tiles straight into LDS where measured faster
-                                  // (AMDP_GEMM_DIRECT=0: never, always through registers; 2: wherever the shape allows)
+                                  // (AMDP_OPT_GEMM_DIRECT_TO_LDS; 0: never, always through registers; 2: wherever the shape allows)
     Profiler prof;
     // Launch target of the helper functions: the caller's stream, or the side
     // stream while a gradient leaf (dW GEMM, bias / LayerNorm column sums) is
@@ -256,7 +256,7 @@ struct amdp_stage {
     // forward that reuses the activation slot they read; both wait for the event
     // recorded behind the leaves, nothing else does. free_seq orders free slots so
     // that a forward takes the one whose leaves are oldest.
-    bool lazy_join = true;           // AMDP_LAZY_JOIN=0: backward ends with a full join (measurement)
+    bool lazy_join = true;           // AMDP_OPT_LAZY_JOIN; false: backward ends with a full join (measurement)
     hipEvent_t input_ev = nullptr;   // behind the leaves that read the caller's dY
     hipEvent_t leaves_ev[MAX_ASLOTS] = {};
     bool leaves_pending[MAX_ASLOTS] = {};
